@@ -1,0 +1,170 @@
+/* spec.h -- C ABI of the MI355X draft + verify library (libspecdraft.so).
+ *
+ * One speculative-decoding step of the combined token/embedding speculator of
+ * arXiv 2404.19124:  spec_draft runs the n-stage MLP speculator and emits the
+ * pruned candidate tree (Sec. 3.1, 4.1 of the paper); spec_verify compares the
+ * base model's logits over the flattened candidates with the speculated tokens
+ * and emits the accepted tokens plus one bonus token (Sec. 1, 3.1, 5).
+ *
+ * Conventions
+ *  - Plain C.  No exception crosses the boundary.  Every entry point checks its
+ *    arguments on the host and returns a negative status BEFORE any HIP call;
+ *    the message is available from spec_last_error() (thread-local).
+ *  - Pointers marked "dev" are device pointers on the current HIP device, owned
+ *    by the caller.  Pointers marked "host" are ordinary host pointers.
+ *  - spec_draft and spec_verify only enqueue work on `hip_stream` (a
+ *    hipStream_t passed as void*; NULL is the default stream).  They never
+ *    synchronise and never allocate.  Outputs are valid once the stream has
+ *    reached the end of the enqueued work.
+ *  - A HIP runtime failure is reported as SPEC_EHIP with the HIP error string.
+ *  - All matrices are row-major with the last index contiguous.
+ */
+#ifndef SPEC_DRAFT_H_
+#define SPEC_DRAFT_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPEC_MAX_STAGES 8      /* n_predict <= 8 (the paper uses 3, 5 and 7) */
+#define SPEC_MAX_TOPK 8        /* branches per head <= 8 (the paper uses up to 6) */
+#define SPEC_MAX_LEAVES 4096   /* prod(top_k) <= 4096 per sequence */
+
+typedef struct spec_model spec_model_t; /* opaque: packed weights, descriptors, workspace */
+
+typedef enum { SPEC_F32 = 0, SPEC_BF16 = 1 } spec_dtype_t;
+
+typedef enum {
+  SPEC_OK = 0,
+  SPEC_EINVAL = -1, /* null pointer, value out of range */
+  SPEC_ESHAPE = -2, /* sizes inconsistent with the model or with each other */
+  SPEC_EDTYPE = -3, /* unknown or unsupported element type */
+  SPEC_ENOMEM = -4, /* device allocation failed (spec_create only) */
+  SPEC_EHIP = -5    /* HIP runtime error */
+} spec_status_t;
+
+/* Shape of the speculator (Sec. 3.1: n stages; Sec. 4: latent width; Sec. 4.2:
+ * only the first stage's input width follows the base model). */
+typedef struct {
+  int32_t n_predict;    /* n: stages = speculated tokens per candidate, 1..SPEC_MAX_STAGES */
+  int32_t emb_dim;      /* E: width of the base model's hidden vector (input of stage 1) */
+  int32_t inner_dim;    /* D: latent width of the speculator */
+  int32_t vocab;        /* V */
+  int32_t weight_dtype; /* spec_dtype_t: storage type of projection / head / embedding
+                           weights, of the input state and of the stage states.
+                           SPEC_BF16 needs E and D to be multiples of 32. */
+  float state_weight;   /* w_s: weight of the projected state in the pair (Sec. 4).  If
+                           state_weight < 0 or emb_weight < 0 both take the closed form of the
+                           50%-variance rule:  w_s = 0.5^(1/2n), w_e = sqrt(1 - 0.5^(1/n)). */
+  float emb_weight;     /* w_e: weight of the token embedding in the pair */
+  float ln_eps;         /* LayerNorm epsilon (inside the root); <= 0 selects 1e-5 */
+  int32_t max_batch;    /* largest batch spec_draft will be called with (sizes the workspace) */
+  int32_t max_top_k[SPEC_MAX_STAGES]; /* per stage, largest top_k[i] spec_draft will be called
+                           with; entries 0..n_predict-1 in 1..SPEC_MAX_TOPK */
+} spec_config_t;
+
+/* Per-stage weights: host arrays of length n_predict holding dev pointers.
+ *   proj[i]     [D, in_i]  (in_0 = E, else D)   weight_dtype   state projection W_i
+ *   emb[i]      [V, D]                          weight_dtype   token embedding table
+ *   head[i]     [V, D]                          weight_dtype   vocabulary head
+ *   ln_gamma[i] [D], ln_beta[i] [D]             float32        LayerNorm affine
+ * The paper ties nothing across stages (Sec. 3.1); passing the same pointer for
+ * several stages gives its weight-tied (RNN) variant.
+ * Ownership: proj and head are COPIED by spec_create into library-owned buffers
+ * (for SPEC_BF16 in a tiled layout that matches the matrix-core operand order),
+ * the caller may release them once spec_create has returned.  emb, ln_gamma and
+ * ln_beta are BORROWED and must stay valid and unchanged until spec_destroy. */
+typedef struct {
+  const void* const* proj;
+  const void* const* emb;
+  const void* const* head;
+  const float* const* ln_gamma;
+  const float* const* ln_beta;
+} spec_weights_t;
+
+/* Optional per-stage intermediates for parity checks (all dev, caller-allocated,
+ * each pointer may be NULL).  Stage i occupies rows [sum_{j<i} R_j, +R_i) with
+ * R_i = batch * prod_{j<i} top_k[j]; rows are sequence-major, then by the ranks
+ * chosen at the earlier stages (node r has children r*k_i + j). */
+typedef struct {
+  void* stage_state;  /* [sum R_i, D] weight_dtype: state of every node */
+  int32_t* topk_tok;  /* concatenated per stage [R_i, k_i]: tokens, most likely first */
+  float* topk_logp;   /* same layout: their log-probabilities */
+  float* row_lse;     /* [sum R_i]: log-sum-exp of every row's logits */
+} spec_debug_t;
+
+/* Builds a model: validates, copies / tiles proj and head, allocates the
+ * workspace for (max_batch, max_top_k).  Uses `hip_stream` for the copies and
+ * synchronises it before returning.  *out is set only on SPEC_OK. */
+spec_status_t spec_create(const spec_config_t* cfg /* host */, const spec_weights_t* w /* host */,
+                          void* hip_stream, spec_model_t** out /* host */);
+
+/* Releases everything spec_create allocated.  NULL is allowed.  The caller must
+ * make sure no enqueued work still uses the model. */
+void spec_destroy(spec_model_t* m);
+
+/* DRAFT (Sec. 3.1, 4.1).  For each of `batch` sequences: starting from the base
+ * model's last hidden vector and the token it just sampled, stage i computes
+ *     state_i = GELU(LayerNorm(w_s * W_i state_{i-1} + w_e * Emb_i[token_{i-1}]))
+ * for every node of depth i-1, takes the top_k[i] most likely tokens of
+ * log_softmax(Head_i state_i) as that node's children, and after n stages keeps
+ * the B leaves with the largest summed log-probability.
+ *   state     dev [batch, E] weight_dtype      base model's last hidden vector
+ *   last_tok  dev [batch] int32 in [0, V)      token the base model just sampled
+ *   top_k     host [n_predict]                 1 <= top_k[i] <= max_top_k[i], <= V
+ *   B                                          1 <= B <= prod(top_k) <= SPEC_MAX_LEAVES
+ * Outputs (dev, caller-allocated):
+ *   cand_tokens [batch, B, n_predict] int32    candidates, most confident first
+ *   cand_scores [batch, B] float32             summed log-probability, descending
+ *   cand_leaf   [batch, B] int32               leaf index, mixed radix over the ranks
+ *                                              (first stage most significant)
+ *   dbg        host, may be NULL
+ * Ties: larger value first, then smaller token id / leaf index.
+ * Errors: SPEC_EINVAL (null, range), SPEC_ESHAPE (exceeds what the model was created for).
+ * Calls on one model must not overlap in time: they share the model's workspace. */
+spec_status_t spec_draft(spec_model_t* m, const void* state, const int32_t* last_tok, int32_t batch,
+                         const int32_t* top_k, int32_t B, int32_t* cand_tokens, float* cand_scores,
+                         int32_t* cand_leaf, const spec_debug_t* dbg, void* hip_stream);
+
+/* VERIFY (Sec. 1, 3.1, 4.1, 5), greedy.
+ *   base_logits dev [batch, B, n_predict+1, V] logits_dtype   position p of candidate c is the
+ *               base model's output after (last token, cand[c, :p]); position n_predict has
+ *               no speculated token and only supplies the bonus token
+ *   cand_tokens dev [batch, B, n_predict] int32
+ * Outputs (dev, caller-allocated):
+ *   greedy      [batch, B, n_predict+1] int32   argmax over V (first maximum); REQUIRED
+ *   accept_len  [batch] int32 in [0, n_predict] longest matching prefix of the best candidate
+ *   best_cand   [batch] int32 in [0, B)         candidate with the longest prefix (first such)
+ *   out_tokens  [batch, n_predict+1] int32      accepted tokens, then the base model's own
+ *                                               token at the first position not accepted, then -1
+ *   n_out       [batch] int32 = accept_len + 1
+ *   accept_all  [batch, B] int32, may be NULL   accepted length of every candidate
+ * The caller picks the base model's hidden vector at (best_cand, accept_len) as the next
+ * step's state and out_tokens[n_out-1] as its last token. */
+spec_status_t spec_verify(const void* base_logits, int32_t logits_dtype, const int32_t* cand_tokens,
+                          int32_t batch, int32_t B, int32_t n_predict, int32_t vocab, int32_t* greedy,
+                          int32_t* accept_len, int32_t* best_cand, int32_t* out_tokens, int32_t* n_out,
+                          int32_t* accept_all, void* hip_stream);
+
+/* Parity aid: full log-softmax rows of stage `stage`'s head for given states,
+ * computed by the same contraction kernels as spec_draft with a store epilogue.
+ *   states dev [rows, D] weight_dtype;  logp dev [rows, V] float32;  rows <= max rows of the model. */
+spec_status_t spec_head_logp(spec_model_t* m, int32_t stage, const void* states, int32_t rows,
+                             float* logp, void* hip_stream);
+
+/* Reads back the mix weights and epsilon the model uses (after defaults were applied). */
+spec_status_t spec_model_scalars(const spec_model_t* m, float* state_weight, float* emb_weight,
+                                 float* ln_eps);
+
+/* Last error message of the calling thread (static storage, never NULL). */
+const char* spec_last_error(void);
+
+/* Library version. */
+spec_status_t spec_version(int32_t* major, int32_t* minor);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPEC_DRAFT_H_ */

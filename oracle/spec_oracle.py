@@ -185,7 +185,7 @@ def draft(weights: dict, state: np.ndarray, last_tok: np.ndarray, top_k: Sequenc
     for i in range(n):
         pz = project(s_prev, weights["proj"][i])                     # one row per distinct parent
         parent = np.arange(node_tok.shape[0]) // k_prev              # siblings share the parent state
-        e = np.asarray(weights["emb"][i], F64)[node_tok]
+        e = np.asarray(weights["emb"][i][node_tok], F64)            # embedding rows of the carried tokens
         s = stage_state(pz[parent], e, weights["ln_gamma"][i], weights["ln_beta"][i],
                         w_s, w_e, eps, state_dtype)
         logits = head_logits(s, weights["head"][i])
@@ -321,7 +321,7 @@ def logp_along_path(weights: dict, state_row: np.ndarray, last_tok: int, path: S
     logp = None
     for i, t in enumerate(toks):
         pz = project(s, weights["proj"][i])
-        e = np.asarray(weights["emb"][i], F64)[[t]]
+        e = np.asarray(weights["emb"][i][[t]], F64)
         s = stage_state(pz, e, weights["ln_gamma"][i], weights["ln_beta"][i], w_s, w_e, eps, state_dtype)
         logp, _ = log_softmax(head_logits(s, weights["head"][i]))
     return s[0], logp[0]

@@ -1,0 +1,206 @@
+// Stage kernel (Sec. 3.1 of the paper): for every node of the current depth,
+//   state = GELU(LayerNorm(w_s * (W s_parent) + w_e * Emb[token]))
+// The token a node carries is the j-th best of its parent's head row; that row's
+// partial results are merged here (every sibling repeats the small merge, which
+// saves a separate launch on the latency-critical batch-1 chain).
+#include "merge.h"
+#include "spec_internal.h"
+
+namespace specdraft {
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void stage_kernel(StageJob j) {
+  extern __shared__ float smem[];
+  float* z = smem;              // [D]
+  float* scratch = smem + j.D;  // [8]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int r = blockIdx.x;
+  const int parent = r / j.k_prev, rank = r - parent * j.k_prev;
+  const int D = j.D;
+
+  int tok;
+  if (j.stage == 0) {
+    tok = j.last_tok[r];
+  } else {
+    float v[kMaxTopK];
+    int32_t ix[kMaxTopK];
+    float lse;
+    wave_merge_partials(j.part, parent, j.nparts, j.k_prev, v, ix, lse);
+    tok = ix[0];
+#pragma unroll
+    for (int q = 1; q < kMaxTopK; ++q)
+      if (q == rank) tok = ix[q];
+    if (rank == 0 && tid < 64) {
+#pragma unroll
+      for (int q = 0; q < kMaxTopK; ++q)
+        if (lane == q && q < j.k_prev) {
+          j.prev_tok[(int64_t)parent * j.k_prev + q] = ix[q];
+          j.prev_logp[(int64_t)parent * j.k_prev + q] = v[q] - lse;
+        }
+      if (lane == 0) j.prev_lse[parent] = lse;
+    }
+  }
+  tok = min(max(tok, 0), j.V - 1);  // a wild token from the caller must not leave the table
+
+  // gather + mix, 8 elements per thread per pass
+  const float* pz = j.pz + (int64_t)parent * D;
+  float lsum = 0.f;
+  for (int c = tid; c < D / 8; c += 256) {
+    const float4 p0 = *reinterpret_cast<const float4*>(pz + c * 8);
+    const float4 p1 = *reinterpret_cast<const float4*>(pz + c * 8 + 4);
+    float e[8];
+    if (BF16) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(j.emb) + (int64_t)tok * D + c * 8);
+      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        e[2 * q] = bf16_bits_to_f32(w[q] & 0xffffu);
+        e[2 * q + 1] = bf16_bits_to_f32(w[q] >> 16);
+      }
+    } else {
+      const float* er = static_cast<const float*>(j.emb) + (int64_t)tok * D + c * 8;
+      const float4 e0 = *reinterpret_cast<const float4*>(er);
+      const float4 e1 = *reinterpret_cast<const float4*>(er + 4);
+      e[0] = e0.x; e[1] = e0.y; e[2] = e0.z; e[3] = e0.w;
+      e[4] = e1.x; e[5] = e1.y; e[6] = e1.z; e[7] = e1.w;
+    }
+    const float p[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const float zz = j.w_s * p[q] + j.w_e * e[q];
+      z[c * 8 + q] = zz;
+      lsum += zz;
+    }
+  }
+  const float mean = block_sum<256>(lsum, scratch) / (float)D;
+  float lvar = 0.f;
+  for (int c = tid; c < D / 8; c += 256) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const float d = z[c * 8 + q] - mean;
+      lvar += d * d;
+    }
+  }
+  const float var = block_sum<256>(lvar, scratch) / (float)D;
+  const float rstd = 1.0f / sqrtf(var + j.eps);
+
+  for (int c = tid; c < D / 8; c += 256) {
+    const float4 g0 = *reinterpret_cast<const float4*>(j.gamma + c * 8);
+    const float4 g1 = *reinterpret_cast<const float4*>(j.gamma + c * 8 + 4);
+    const float4 b0 = *reinterpret_cast<const float4*>(j.beta + c * 8);
+    const float4 b1 = *reinterpret_cast<const float4*>(j.beta + c * 8 + 4);
+    const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+    const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+    float s[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const float y = (z[c * 8 + q] - mean) * rstd * g[q] + b[q];
+      s[q] = 0.5f * y * (1.0f + erff(y * 0.70710678118654752440f));
+    }
+    if (BF16) {
+      uint4 o;
+      o.x = f32_to_bf16_bits(s[0]) | (f32_to_bf16_bits(s[1]) << 16);
+      o.y = f32_to_bf16_bits(s[2]) | (f32_to_bf16_bits(s[3]) << 16);
+      o.z = f32_to_bf16_bits(s[4]) | (f32_to_bf16_bits(s[5]) << 16);
+      o.w = f32_to_bf16_bits(s[6]) | (f32_to_bf16_bits(s[7]) << 16);
+      // tiled layout: row tile r/16, column fragment c/4, lane slot (c%4)*16 + r%16
+      const int64_t slot = ((int64_t)(r >> 4) * (D / 32) + (c >> 2)) * 64 + ((c & 3) << 4) + (r & 15);
+      reinterpret_cast<uint4*>(j.state_out)[slot] = o;
+      if (j.state_dbg) reinterpret_cast<uint4*>(j.state_dbg)[((int64_t)r * D) / 8 + c] = o;
+    } else {
+      float* so = static_cast<float*>(j.state_out) + (int64_t)r * D + c * 8;
+      *reinterpret_cast<float4*>(so) = make_float4(s[0], s[1], s[2], s[3]);
+      *reinterpret_cast<float4*>(so + 4) = make_float4(s[4], s[5], s[6], s[7]);
+      if (j.state_dbg) {
+        float* sd = static_cast<float*>(j.state_dbg) + (int64_t)r * D + c * 8;
+        *reinterpret_cast<float4*>(sd) = make_float4(s[0], s[1], s[2], s[3]);
+        *reinterpret_cast<float4*>(sd + 4) = make_float4(s[4], s[5], s[6], s[7]);
+      }
+    }
+  }
+}
+
+hipError_t launch_stage(const StageJob& job, hipStream_t st) {
+  const size_t smem = (size_t)(job.D + 8) * sizeof(float);
+  if (job.bf16)
+    hipLaunchKernelGGL(stage_kernel<true>, dim3(job.R), dim3(256), smem, st, job);
+  else
+    hipLaunchKernelGGL(stage_kernel<false>, dim3(job.R), dim3(256), smem, st, job);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Tree kernel (Sec. 3.1, 4.1): merge the last head's partial results, score
+// every leaf by the sum of its tokens' log-probabilities (added in stage order),
+// keep the B best.  One workgroup per sequence.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void tree_kernel(TreeJob j) {
+  __shared__ float sc[kMaxLeaves];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int q = blockIdx.x;
+  const int n = j.n, L = j.L;
+  const int k_last = j.top_k[n - 1];
+  const int rows_last = L / k_last;
+
+  for (int rl = wave; rl < rows_last; rl += 4) {
+    const int64_t row = (int64_t)q * rows_last + rl;
+    float v[kMaxTopK];
+    int32_t ix[kMaxTopK];
+    float lse;
+    wave_merge_partials(j.part, row, j.nparts, k_last, v, ix, lse);
+#pragma unroll
+    for (int t = 0; t < kMaxTopK; ++t)
+      if (lane == t && t < k_last) {
+        j.tok[j.off[n - 1] + row * k_last + t] = ix[t];
+        j.logp[j.off[n - 1] + row * k_last + t] = v[t] - lse;
+      }
+    if (lane == 0) j.lse[j.row_off[n - 1] + row] = lse;
+  }
+  __threadfence_block();
+  __syncthreads();
+
+  for (int leaf = tid; leaf < L; leaf += 256) {
+    float score = 0.f;
+    int64_t row = q;
+    int stride = L;
+    for (int i = 0; i < n; ++i) {
+      const int k = j.top_k[i];
+      stride /= k;
+      const int rank = (leaf / stride) % k;
+      score += j.logp[j.off[i] + row * k + rank];
+      row = row * k + rank;
+    }
+    sc[leaf] = score;
+  }
+  __syncthreads();
+
+  for (int leaf = tid; leaf < L; leaf += 256) {
+    const float s = sc[leaf];
+    int pos = 0;
+    for (int o = 0; o < L; ++o) {
+      const float so = sc[o];
+      pos += ((so > s) || (so == s && o < leaf)) ? 1 : 0;
+    }
+    if (pos < j.B) {
+      const int64_t c = (int64_t)q * j.B + pos;
+      j.cand_leaf[c] = leaf;
+      j.cand_scores[c] = s;
+      int64_t row = q;
+      int stride = L;
+      for (int i = 0; i < n; ++i) {
+        const int k = j.top_k[i];
+        stride /= k;
+        const int rank = (leaf / stride) % k;
+        j.cand_tokens[c * n + i] = j.tok[j.off[i] + row * k + rank];
+        row = row * k + rank;
+      }
+    }
+  }
+}
+
+hipError_t launch_tree(const TreeJob& job, hipStream_t st) {
+  hipLaunchKernelGGL(tree_kernel, dim3(job.batch), dim3(256), 0, st, job);
+  return hipGetLastError();
+}
+
+}  // namespace specdraft

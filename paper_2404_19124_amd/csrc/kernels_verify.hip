@@ -1,0 +1,124 @@
+// Verification (Sec. 1, 3.1, 5 of the paper), greedy:
+//   greedy[b,c,p]  = first maximum of base_logits[b,c,p,:]
+//   accept[b,c]    = number of leading positions p with greedy[b,c,p] == cand[b,c,p]
+//   best[b]        = first candidate with the longest accepted prefix
+//   out            = cand[b,best,:a] ++ greedy[b,best,a]   (the bonus token)
+// The row scan is the only part that touches real memory: one workgroup per
+// (b,c,p) row, 16-byte loads, (value, index) reduced with "larger value, then
+// smaller index".
+#include "device_utils.h"
+#include "spec_internal.h"
+
+namespace specdraft {
+
+template <bool BF16, bool VEC>
+__global__ __launch_bounds__(1024) void argmax_rows_kernel(const void* logits, int V, int32_t* greedy) {
+  __shared__ float sv[16];
+  __shared__ int32_t si[16];
+  const int64_t row = blockIdx.x;
+  const int tid = threadIdx.x;
+  float bv = SPEC_NEG_INF;
+  int32_t bi = kIdxNone;
+  if (BF16) {
+    const uint16_t* x = static_cast<const uint16_t*>(logits) + row * V;
+    if (VEC) {
+      const uint4* xv = reinterpret_cast<const uint4*>(x);
+      for (int c = tid; c < V / 8; c += 1024) {
+        const uint4 raw = xv[c];
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float lo = bf16_bits_to_f32(w[q] & 0xffffu), hi = bf16_bits_to_f32(w[q] >> 16);
+          const int i0 = c * 8 + 2 * q;
+          if (before(lo, i0, bv, bi)) { bv = lo; bi = i0; }
+          if (before(hi, i0 + 1, bv, bi)) { bv = hi; bi = i0 + 1; }
+        }
+      }
+      for (int i = (V / 8) * 8 + tid; i < V; i += 1024) {
+        const float v = bf16_bits_to_f32(x[i]);
+        if (before(v, i, bv, bi)) { bv = v; bi = i; }
+      }
+    } else {
+      for (int i = tid; i < V; i += 1024) {
+        const float v = bf16_bits_to_f32(x[i]);
+        if (before(v, i, bv, bi)) { bv = v; bi = i; }
+      }
+    }
+  } else {
+    const float* x = static_cast<const float*>(logits) + row * V;
+    if (VEC) {
+      const float4* xv = reinterpret_cast<const float4*>(x);
+      for (int c = tid; c < V / 4; c += 1024) {
+        const float4 r = xv[c];
+        const float v[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (before(v[q], c * 4 + q, bv, bi)) { bv = v[q]; bi = c * 4 + q; }
+      }
+      for (int i = (V / 4) * 4 + tid; i < V; i += 1024) {
+        const float v = x[i];
+        if (before(v, i, bv, bi)) { bv = v; bi = i; }
+      }
+    } else {
+      for (int i = tid; i < V; i += 1024) {
+        const float v = x[i];
+        if (before(v, i, bv, bi)) { bv = v; bi = i; }
+      }
+    }
+  }
+  block_best<1024>(bv, bi, sv, si);
+  // a row of NaNs (or of -inf) has no "larger" element: report index 0 like a first-maximum scan
+  if (tid == 0) greedy[row] = (bi == kIdxNone) ? 0 : bi;
+}
+
+hipError_t launch_argmax_rows(const void* logits, int bf16, int64_t rows, int V, int32_t* greedy, hipStream_t st) {
+  const size_t esz = bf16 ? 2 : 4;
+  // 16-byte loads need every row to start on a 16-byte boundary
+  const bool vec = ((size_t)V * esz) % 16 == 0 && (reinterpret_cast<uintptr_t>(logits) % 16) == 0;
+  dim3 grid((unsigned)rows), block(1024);
+  if (bf16) {
+    if (vec) hipLaunchKernelGGL((argmax_rows_kernel<true, true>), grid, block, 0, st, logits, V, greedy);
+    else hipLaunchKernelGGL((argmax_rows_kernel<true, false>), grid, block, 0, st, logits, V, greedy);
+  } else {
+    if (vec) hipLaunchKernelGGL((argmax_rows_kernel<false, true>), grid, block, 0, st, logits, V, greedy);
+    else hipLaunchKernelGGL((argmax_rows_kernel<false, false>), grid, block, 0, st, logits, V, greedy);
+  }
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(64) void accept_kernel(const int32_t* greedy, const int32_t* cand, int B, int n,
+                                                    int32_t* accept_len, int32_t* best_cand, int32_t* out_tokens,
+                                                    int32_t* n_out, int32_t* accept_all) {
+  const int q = blockIdx.x, lane = threadIdx.x;
+  // (accepted length, candidate): longer first, then smaller candidate index
+  float bv = -1.f;
+  int32_t bi = kIdxNone;
+  for (int c = lane; c < B; c += 64) {
+    const int32_t* g = greedy + ((int64_t)q * B + c) * (n + 1);
+    const int32_t* t = cand + ((int64_t)q * B + c) * n;
+    int a = 0;
+    while (a < n && g[a] == t[a]) ++a;
+    if (accept_all) accept_all[(int64_t)q * B + c] = a;
+    if (before((float)a, c, bv, bi)) { bv = (float)a; bi = c; }
+  }
+  wave_best(bv, bi);
+  const int a = (int)bv, best = bi;
+  if (lane == 0) {
+    accept_len[q] = a;
+    best_cand[q] = best;
+    n_out[q] = a + 1;
+  }
+  const int32_t* g = greedy + ((int64_t)q * B + best) * (n + 1);
+  const int32_t* t = cand + ((int64_t)q * B + best) * n;
+  for (int p = lane; p <= n; p += 64) out_tokens[(int64_t)q * (n + 1) + p] = p < a ? t[p] : (p == a ? g[a] : -1);
+}
+
+hipError_t launch_accept(const int32_t* greedy, const int32_t* cand, int batch, int B, int n, int32_t* accept_len,
+                         int32_t* best_cand, int32_t* out_tokens, int32_t* n_out, int32_t* accept_all,
+                         hipStream_t st) {
+  hipLaunchKernelGGL(accept_kernel, dim3(batch), dim3(64), 0, st, greedy, cand, B, n, accept_len, best_cand,
+                     out_tokens, n_out, accept_all);
+  return hipGetLastError();
+}
+
+}  // namespace specdraft

@@ -1,0 +1,138 @@
+// Internal declarations shared by the HIP translation units of libspecdraft.
+// Not part of the public boundary (that is include/spec.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace specdraft {
+
+constexpr int kMaxTopK = 8;       // = SPEC_MAX_TOPK
+constexpr int kMaxStages = 8;     // = SPEC_MAX_STAGES
+constexpr int kMaxLeaves = 4096;  // = SPEC_MAX_LEAVES
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+// ---------------------------------------------------------------------------
+// Tiled ("packed") bf16 layout.  A row-major matrix X[N][K] (K % 32 == 0) is
+// stored as fragments of 16 rows x 32 columns, each fragment being exactly the
+// per-lane operand order of v_mfma_f32_16x16x32_bf16:
+//     slot(nt, t, lane) = 8 consecutive bf16 = X[nt*16 + lane%16][t*32 + (lane/16)*8 .. +8)
+//     address (in 16-byte slots) = (nt * (K/32) + t) * 64 + lane
+// so that a wave reads one fragment as one fully coalesced 1 KiB access.  Rows
+// beyond N are zero (weights) or unspecified (states).
+// ---------------------------------------------------------------------------
+
+// Partial result of a head contraction for one (row, part): the running maximum
+// and sum of exponentials of the logits seen by that part, and its k largest
+// logits with their vocabulary indices (descending, ties by smaller index).
+// Storage: m, s at [row * nparts + part]; val, idx at [(row * nparts + part) * k + j].
+struct Partials {
+  float* m;
+  float* s;
+  float* val;
+  int32_t* idx;
+};
+
+// ---- packing --------------------------------------------------------------
+// src row-major [n_rows][k] bf16 -> dst packed with ceil(n_rows/16) row tiles.
+hipError_t launch_pack_bf16(const void* src, void* dst, int n_rows, int k, bool zero_pad, hipStream_t st);
+
+// ---- contraction, bf16 on the matrix cores --------------------------------
+struct HeadJob {
+  // weights (packed): `n_head` valid rows in `vt_head` tiles, then optionally a
+  // second matrix (the next stage's projection) of `n_proj` rows in `vt_proj` tiles.
+  const void* w_head;
+  int vt_head, n_head;
+  const void* w_proj;
+  int vt_proj, n_proj;
+  int kt;                 // K / 32
+  // states: R rows; packed (one or more 16-row tiles) or row-major bf16 [R][ld]
+  const void* b_src;
+  int b_rowmajor, b_ld, R;
+  // head epilogue: top-k partials (k_top entries) unless out_head != nullptr,
+  // in which case raw logits are stored to out_head[r * ld_head + v]
+  int k_top;
+  Partials part;
+  int nparts;
+  float* out_head;
+  int64_t ld_head;
+  // projection epilogue: out_proj[r * ld_proj + d]
+  float* out_proj;
+  int64_t ld_proj;
+};
+
+// Rows <= 16: one persistent workgroup per CU, K split over its 16 waves,
+// weights streamed tile by tile straight into registers.  nparts = grid size.
+bool skinny_fits(int R, int kt);
+int skinny_grid(int n_cu);
+hipError_t launch_head_skinny(const HeadJob& job, int n_cu, hipStream_t st);
+
+// Any number of rows: workgroup tiles of (16*MI rows) x (64*NI weight rows).
+// One matrix per launch (head with top-k partials or store; or projection store).
+struct GemmPlan {
+  int mi, ni;       // fragments per wave in M (state rows) and N (weight rows)
+  int m_tiles, n_tiles;
+};
+GemmPlan plan_gemm(int R, int n_rows_weight);
+hipError_t launch_head_gemm(const HeadJob& job, bool proj_matrix, const GemmPlan& plan, hipStream_t st);
+
+// ---- contraction, float32 (correctness configuration) ---------------------
+// out[r * ldo + v] = sum_k a[r * lda + k] * w[v * ldw + k]
+hipError_t launch_gemm_f32(const float* a, int64_t lda, const float* w, int64_t ldw, float* out, int64_t ldo,
+                           int R, int N, int K, hipStream_t st);
+// one partial per row from materialised logits [R][ld]
+hipError_t launch_row_topk_f32(const float* logits, int64_t ld, int R, int V, int k_top, Partials part,
+                               hipStream_t st);
+// logp[r][v] = logits[r][v] - logsumexp(logits[r])   (in place allowed)
+hipError_t launch_row_log_softmax(const float* logits, float* logp, int64_t ld, int R, int V, hipStream_t st);
+
+// ---- stage: merge of the previous head's partials + gather + mix + LN + GELU
+struct StageJob {
+  int stage;               // 0-based
+  int R;                   // child rows of this stage
+  int k_prev;              // top_k of the previous stage (1 for stage 0)
+  int D;
+  int bf16;                // weight / state storage type
+  // previous head (stage > 0)
+  Partials part;
+  int nparts, V;
+  int32_t* prev_tok;       // [R/k_prev][k_prev] out
+  float* prev_logp;        // same layout, out
+  float* prev_lse;         // [R/k_prev] out
+  const int32_t* last_tok; // stage 0: [R]
+  const float* pz;         // [R/k_prev][D] projected parent state
+  const void* emb;         // [V][D]
+  const float* gamma;
+  const float* beta;
+  float w_s, w_e, eps;
+  void* state_out;         // bf16: packed tiles; f32: row-major [R][D]
+  void* state_dbg;         // optional row-major [R][D] copy in the storage type
+};
+hipError_t launch_stage(const StageJob& job, hipStream_t st);
+
+// ---- tree: merge of the last head + leaf scores + top-B ----------------------
+struct TreeJob {
+  int batch, n, B, L;
+  int top_k[kMaxStages];
+  Partials part;           // last head
+  int nparts;
+  // per-stage tables [R_i][k_i], concatenated; offsets in elements
+  int32_t* tok;
+  float* logp;
+  float* lse;              // [sum R_i]
+  int64_t off[kMaxStages]; // element offset of stage i in tok / logp
+  int64_t row_off[kMaxStages];
+  int32_t* cand_tokens;
+  float* cand_scores;
+  int32_t* cand_leaf;
+};
+hipError_t launch_tree(const TreeJob& job, hipStream_t st);
+
+// ---- verify ----------------------------------------------------------------
+hipError_t launch_argmax_rows(const void* logits, int bf16, int64_t rows, int V, int32_t* greedy, hipStream_t st);
+hipError_t launch_accept(const int32_t* greedy, const int32_t* cand, int batch, int B, int n, int32_t* accept_len,
+                         int32_t* best_cand, int32_t* out_tokens, int32_t* n_out, int32_t* accept_all,
+                         hipStream_t st);
+
+}  // namespace specdraft

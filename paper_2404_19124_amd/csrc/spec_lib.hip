@@ -1,0 +1,488 @@
+// C ABI of libspecdraft (declared in include/spec.h): argument validation,
+// model / workspace ownership and the launch sequence of one draft and one
+// verify.  All arithmetic lives in the kernels_*.hip files.
+#include "../../include/spec.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "spec_internal.h"
+
+using namespace specdraft;
+
+static_assert(SPEC_MAX_TOPK == kMaxTopK, "header and kernels disagree");
+static_assert(SPEC_MAX_STAGES == kMaxStages, "header and kernels disagree");
+static_assert(SPEC_MAX_LEAVES == kMaxLeaves, "header and kernels disagree");
+
+static thread_local char g_err[512] = "";
+
+static spec_status_t fail(spec_status_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+static spec_status_t hip_fail(hipError_t e, const char* what) {
+  return fail(SPEC_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+#define HIP_TRY(expr)                                  \
+  do {                                                 \
+    hipError_t e_ = (expr);                            \
+    if (e_ != hipSuccess) return hip_fail(e_, #expr);  \
+  } while (0)
+
+struct spec_model {
+  spec_config_t cfg;
+  float w_s, w_e, eps;
+  int n_cu;
+  bool bf16;
+  size_t esz;
+  // library-owned copies of the contraction weights (bf16: tiled; f32: row-major)
+  void* proj[kMaxStages];
+  void* head[kMaxStages];
+  // borrowed
+  const void* emb[kMaxStages];
+  const float* gamma[kMaxStages];
+  const float* beta[kMaxStages];
+  // workspace
+  int64_t max_rows;          // largest R_i
+  int64_t max_parent_rows;   // largest number of distinct parent states
+  int64_t sum_rows, sum_rows_k;
+  void* state_in;            // bf16: tiled copy of the caller's state (batch > 16)
+  void* states;              // current stage's states (tiled bf16 / row-major f32)
+  float* pz[2];              // projected parent states, ping-pong
+  Partials part;
+  int64_t part_rows_parts;   // capacity in (row, part) slots
+  int32_t* tok;              // per-stage top-k tables, concatenated
+  float* logp;
+  float* lse;
+  float* logits;             // f32 path and spec_head_logp: materialised rows
+  int64_t logits_rows;
+  std::vector<void*> owned;
+};
+
+static void free_model(spec_model* m) {
+  if (!m) return;
+  for (void* p : m->owned)
+    if (p) (void)hipFree(p);
+  delete m;
+}
+
+template <typename T>
+static spec_status_t dev_alloc(spec_model* m, T** out, size_t bytes) {
+  void* p = nullptr;
+  hipError_t e = hipMalloc(&p, bytes ? bytes : 16);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(SPEC_ENOMEM, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+  }
+  m->owned.push_back(p);
+  *out = static_cast<T*>(p);
+  return SPEC_OK;
+}
+
+static spec_status_t check_config(const spec_config_t* c) {
+  if (!c) return fail(SPEC_EINVAL, "cfg is NULL");
+  if (c->n_predict < 1 || c->n_predict > SPEC_MAX_STAGES)
+    return fail(SPEC_EINVAL, "n_predict = %d outside [1, %d]", c->n_predict, SPEC_MAX_STAGES);
+  if (c->emb_dim < 1 || c->inner_dim < 1 || c->vocab < 1)
+    return fail(SPEC_EINVAL, "emb_dim, inner_dim and vocab must be positive");
+  if (c->weight_dtype != SPEC_F32 && c->weight_dtype != SPEC_BF16)
+    return fail(SPEC_EDTYPE, "weight_dtype = %d is neither SPEC_F32 nor SPEC_BF16", c->weight_dtype);
+  if (c->weight_dtype == SPEC_BF16 && (c->emb_dim % 64 || c->inner_dim % 64))
+    return fail(SPEC_ESHAPE, "SPEC_BF16 needs emb_dim and inner_dim to be multiples of 64 (got %d, %d)", c->emb_dim,
+                c->inner_dim);
+  if (c->weight_dtype == SPEC_F32 && (c->inner_dim % 8))
+    return fail(SPEC_ESHAPE, "SPEC_F32 needs inner_dim to be a multiple of 8 (got %d)", c->inner_dim);
+  if (c->max_batch < 1) return fail(SPEC_EINVAL, "max_batch must be >= 1");
+  int64_t leaves = 1, rows = c->max_batch;
+  for (int i = 0; i < c->n_predict; ++i) {
+    const int k = c->max_top_k[i];
+    if (k < 1 || k > SPEC_MAX_TOPK) return fail(SPEC_EINVAL, "max_top_k[%d] = %d outside [1, %d]", i, k, SPEC_MAX_TOPK);
+    if (k > c->vocab) return fail(SPEC_EINVAL, "max_top_k[%d] = %d exceeds vocab = %d", i, k, c->vocab);
+    leaves *= k;
+    if (i + 1 < c->n_predict) rows *= k;
+    if (leaves > SPEC_MAX_LEAVES) return fail(SPEC_ESHAPE, "prod(max_top_k) exceeds %d leaves", SPEC_MAX_LEAVES);
+    if (rows > (1 << 24)) return fail(SPEC_ESHAPE, "max_batch * prod(max_top_k) is too large");
+  }
+  if (!std::isfinite(c->state_weight) || !std::isfinite(c->emb_weight) || !std::isfinite(c->ln_eps))
+    return fail(SPEC_EINVAL, "state_weight, emb_weight and ln_eps must be finite");
+  return SPEC_OK;
+}
+
+// capacity (in (row, part) slots) that covers every contraction plan a call may pick
+static int64_t partial_capacity(int64_t max_rows, int V, int n_cu) {
+  int64_t cap = 16 * (int64_t)skinny_grid(n_cu);
+  for (int64_t R : {(int64_t)32, (int64_t)64, max_rows}) {
+    const int64_t r = R < max_rows ? R : max_rows;
+    GemmPlan pl = plan_gemm((int)r, V);
+    const int64_t c = r * pl.n_tiles;
+    if (c > cap) cap = c;
+  }
+  if (max_rows > cap) cap = max_rows;  // f32 path: one part per row
+  return cap;
+}
+
+extern "C" spec_status_t spec_create(const spec_config_t* cfg, const spec_weights_t* w, void* hip_stream,
+                                     spec_model_t** out) {
+  spec_status_t st = check_config(cfg);
+  if (st != SPEC_OK) return st;
+  if (!w || !out) return fail(SPEC_EINVAL, "weights or out is NULL");
+  if (!w->proj || !w->emb || !w->head || !w->ln_gamma || !w->ln_beta)
+    return fail(SPEC_EINVAL, "a per-stage pointer array of the weights is NULL");
+  for (int i = 0; i < cfg->n_predict; ++i)
+    if (!w->proj[i] || !w->emb[i] || !w->head[i] || !w->ln_gamma[i] || !w->ln_beta[i])
+      return fail(SPEC_EINVAL, "a weight pointer of stage %d is NULL", i);
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  spec_model* m = new (std::nothrow) spec_model();
+  if (!m) return fail(SPEC_ENOMEM, "host allocation failed");
+  m->cfg = *cfg;
+  const int n = cfg->n_predict, E = cfg->emb_dim, D = cfg->inner_dim, V = cfg->vocab;
+  if (cfg->state_weight < 0.f || cfg->emb_weight < 0.f) {
+    m->w_s = (float)std::pow(0.5, 1.0 / (2.0 * n));
+    m->w_e = (float)std::sqrt(1.0 - std::pow(0.5, 1.0 / n));
+  } else {
+    m->w_s = cfg->state_weight;
+    m->w_e = cfg->emb_weight;
+  }
+  m->eps = cfg->ln_eps > 0.f ? cfg->ln_eps : 1e-5f;
+  m->bf16 = cfg->weight_dtype == SPEC_BF16;
+  m->esz = m->bf16 ? 2 : 4;
+
+  int dev = 0;
+  hipDeviceProp_t prop;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+  if (e != hipSuccess) {
+    free_model(m);
+    return hip_fail(e, "hipGetDeviceProperties");
+  }
+  m->n_cu = prop.multiProcessorCount;
+
+  // rows per stage at the largest call
+  int64_t rows = cfg->max_batch, sum_rows = 0, sum_rows_k = 0, max_rows = 0, max_parent = cfg->max_batch;
+  for (int i = 0; i < n; ++i) {
+    if (rows > max_rows) max_rows = rows;
+    if (i + 1 < n && rows > max_parent) max_parent = rows;
+    sum_rows += rows;
+    sum_rows_k += rows * cfg->max_top_k[i];
+    rows *= cfg->max_top_k[i];
+  }
+  m->max_rows = max_rows;
+  m->max_parent_rows = max_parent;
+  m->sum_rows = sum_rows;
+  m->sum_rows_k = sum_rows_k;
+
+#define TRY_FREE(expr)          \
+  do {                          \
+    spec_status_t s_ = (expr);  \
+    if (s_ != SPEC_OK) {        \
+      free_model(m);            \
+      return s_;                \
+    }                           \
+  } while (0)
+#define HIP_TRY_FREE(expr)              \
+  do {                                  \
+    hipError_t e_ = (expr);             \
+    if (e_ != hipSuccess) {             \
+      free_model(m);                    \
+      return hip_fail(e_, #expr);       \
+    }                                   \
+  } while (0)
+
+  for (int i = 0; i < n; ++i) {
+    const int in = i == 0 ? E : D;
+    m->emb[i] = w->emb[i];
+    m->gamma[i] = w->ln_gamma[i];
+    m->beta[i] = w->ln_beta[i];
+    if (m->bf16) {
+      const size_t pb = (size_t)((D + 15) / 16) * 16 * in * 2, hb = (size_t)((V + 15) / 16) * 16 * D * 2;
+      TRY_FREE(dev_alloc(m, &m->proj[i], pb));
+      TRY_FREE(dev_alloc(m, &m->head[i], hb));
+      HIP_TRY_FREE(launch_pack_bf16(w->proj[i], m->proj[i], D, in, true, stream));
+      HIP_TRY_FREE(launch_pack_bf16(w->head[i], m->head[i], V, D, true, stream));
+    } else {
+      TRY_FREE(dev_alloc(m, &m->proj[i], (size_t)D * in * 4));
+      TRY_FREE(dev_alloc(m, &m->head[i], (size_t)V * D * 4));
+      HIP_TRY_FREE(hipMemcpyAsync(m->proj[i], w->proj[i], (size_t)D * in * 4, hipMemcpyDeviceToDevice, stream));
+      HIP_TRY_FREE(hipMemcpyAsync(m->head[i], w->head[i], (size_t)V * D * 4, hipMemcpyDeviceToDevice, stream));
+    }
+  }
+
+  const int64_t rows16 = (max_rows + 15) / 16 * 16, batch16 = ((int64_t)cfg->max_batch + 15) / 16 * 16;
+  TRY_FREE(dev_alloc(m, &m->states, (size_t)rows16 * D * m->esz));
+  TRY_FREE(dev_alloc(m, &m->state_in, m->bf16 ? (size_t)batch16 * E * 2 : 16));
+  HIP_TRY_FREE(hipMemsetAsync(m->states, 0, (size_t)rows16 * D * m->esz, stream));
+  if (m->bf16) HIP_TRY_FREE(hipMemsetAsync(m->state_in, 0, (size_t)batch16 * E * 2, stream));
+  for (int q = 0; q < 2; ++q) TRY_FREE(dev_alloc(m, &m->pz[q], (size_t)max_parent * D * 4));
+  m->part_rows_parts = partial_capacity(max_rows, V, m->n_cu);
+  TRY_FREE(dev_alloc(m, &m->part.m, (size_t)m->part_rows_parts * 4));
+  TRY_FREE(dev_alloc(m, &m->part.s, (size_t)m->part_rows_parts * 4));
+  TRY_FREE(dev_alloc(m, &m->part.val, (size_t)m->part_rows_parts * kMaxTopK * 4));
+  TRY_FREE(dev_alloc(m, &m->part.idx, (size_t)m->part_rows_parts * kMaxTopK * 4));
+  TRY_FREE(dev_alloc(m, &m->tok, (size_t)sum_rows_k * 4));
+  TRY_FREE(dev_alloc(m, &m->logp, (size_t)sum_rows_k * 4));
+  TRY_FREE(dev_alloc(m, &m->lse, (size_t)sum_rows * 4));
+  // materialised logits: every row for the f32 path, a small window otherwise (spec_head_logp)
+  m->logits_rows = m->bf16 ? 0 : max_rows;
+  TRY_FREE(dev_alloc(m, &m->logits, (size_t)m->logits_rows * V * 4));
+
+  HIP_TRY_FREE(hipStreamSynchronize(stream));
+#undef TRY_FREE
+#undef HIP_TRY_FREE
+  *out = m;
+  return SPEC_OK;
+}
+
+extern "C" void spec_destroy(spec_model_t* m) { free_model(m); }
+
+extern "C" spec_status_t spec_model_scalars(const spec_model_t* m, float* state_weight, float* emb_weight,
+                                            float* ln_eps) {
+  if (!m) return fail(SPEC_EINVAL, "model is NULL");
+  if (state_weight) *state_weight = m->w_s;
+  if (emb_weight) *emb_weight = m->w_e;
+  if (ln_eps) *ln_eps = m->eps;
+  return SPEC_OK;
+}
+
+// One contraction of R state rows against head[stage] (top-k partials, or raw
+// logits into out_head) and, if proj_stage >= 0, against proj[proj_stage]
+// (stored to out_proj).  Returns the number of parts per row it produced.
+static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, const void* b_src, bool b_rowmajor,
+                                     int b_ld, int R, int k_top, float* out_head, float* out_proj, int* nparts,
+                                     hipStream_t st) {
+  const int D = m->cfg.inner_dim, V = m->cfg.vocab;
+  HeadJob job;
+  memset(&job, 0, sizeof(job));
+  const int K = b_ld;
+  job.kt = K / 32;
+  job.b_src = b_src;
+  job.b_rowmajor = b_rowmajor ? 1 : 0;
+  job.b_ld = b_ld;
+  job.R = R;
+  job.k_top = k_top;
+  job.part = m->part;
+  job.out_head = out_head;
+  job.ld_head = V;
+  job.out_proj = out_proj;
+  job.ld_proj = D;
+  if (stage >= 0) {
+    job.w_head = m->head[stage];
+    job.vt_head = (V + 15) / 16;
+    job.n_head = V;
+  }
+  if (proj_stage >= 0) {
+    job.w_proj = m->proj[proj_stage];
+    job.vt_proj = (D + 15) / 16;
+    job.n_proj = D;
+  }
+  if (skinny_fits(R, job.kt)) {
+    job.nparts = skinny_grid(m->n_cu);
+    *nparts = job.nparts;
+    HIP_TRY(launch_head_skinny(job, m->n_cu, st));
+    return SPEC_OK;
+  }
+  // general path wants tiled states
+  if (b_rowmajor) {
+    HIP_TRY(launch_pack_bf16(b_src, m->state_in, R, K, false, st));
+    job.b_src = m->state_in;
+    job.b_rowmajor = 0;
+  }
+  *nparts = 1;
+  if (stage >= 0) {
+    GemmPlan pl = plan_gemm(R, V);
+    job.nparts = pl.n_tiles;
+    *nparts = pl.n_tiles;
+    if (!out_head && (int64_t)R * pl.n_tiles > m->part_rows_parts)
+      return fail(SPEC_ESHAPE, "internal: partial workspace too small (%d rows x %d parts)", R, pl.n_tiles);
+    HIP_TRY(launch_head_gemm(job, false, pl, st));
+  }
+  if (proj_stage >= 0) {
+    GemmPlan pl = plan_gemm(R, D);
+    HIP_TRY(launch_head_gemm(job, true, pl, st));
+  }
+  return SPEC_OK;
+}
+
+extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const int32_t* last_tok, int32_t batch,
+                                    const int32_t* top_k, int32_t B, int32_t* cand_tokens, float* cand_scores,
+                                    int32_t* cand_leaf, const spec_debug_t* dbg, void* hip_stream) {
+  if (!m) return fail(SPEC_EINVAL, "model is NULL");
+  if (!state || !last_tok || !top_k || !cand_tokens || !cand_scores || !cand_leaf)
+    return fail(SPEC_EINVAL, "a required pointer is NULL");
+  if (batch < 1) return fail(SPEC_EINVAL, "batch = %d must be >= 1", batch);
+  if (batch > m->cfg.max_batch) return fail(SPEC_ESHAPE, "batch = %d exceeds max_batch = %d", batch, m->cfg.max_batch);
+  const int n = m->cfg.n_predict, E = m->cfg.emb_dim, D = m->cfg.inner_dim, V = m->cfg.vocab;
+  int64_t L = 1;
+  for (int i = 0; i < n; ++i) {
+    if (top_k[i] < 1) return fail(SPEC_EINVAL, "top_k[%d] = %d must be >= 1", i, top_k[i]);
+    if (top_k[i] > m->cfg.max_top_k[i])
+      return fail(SPEC_ESHAPE, "top_k[%d] = %d exceeds max_top_k[%d] = %d", i, top_k[i], i, m->cfg.max_top_k[i]);
+    L *= top_k[i];
+  }
+  if (B < 1 || B > L) return fail(SPEC_EINVAL, "B = %d outside [1, prod(top_k) = %lld]", B, (long long)L);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+  // rows and table offsets per stage
+  int64_t R[kMaxStages], off[kMaxStages], row_off[kMaxStages];
+  {
+    int64_t r = batch, o = 0, ro = 0;
+    for (int i = 0; i < n; ++i) {
+      R[i] = r;
+      off[i] = o;
+      row_off[i] = ro;
+      o += r * top_k[i];
+      ro += r;
+      r *= top_k[i];
+    }
+  }
+
+  int nparts = 1;
+  // projection of the base model's state for stage 1
+  if (m->bf16) {
+    spec_status_t s = run_contraction(m, -1, 0, state, true, E, batch, 0, nullptr, m->pz[0], &nparts, st);
+    if (s != SPEC_OK) return s;
+  } else {
+    HIP_TRY(launch_gemm_f32(static_cast<const float*>(state), E, static_cast<const float*>(m->proj[0]), E, m->pz[0], D,
+                            batch, D, E, st));
+  }
+
+  for (int i = 0; i < n; ++i) {
+    StageJob sj;
+    memset(&sj, 0, sizeof(sj));
+    sj.stage = i;
+    sj.R = (int)R[i];
+    sj.k_prev = i == 0 ? 1 : top_k[i - 1];
+    sj.D = D;
+    sj.bf16 = m->bf16 ? 1 : 0;
+    sj.part = m->part;
+    sj.nparts = nparts;
+    sj.V = V;
+    if (i > 0) {
+      sj.prev_tok = m->tok + off[i - 1];
+      sj.prev_logp = m->logp + off[i - 1];
+      sj.prev_lse = m->lse + row_off[i - 1];
+    }
+    sj.last_tok = last_tok;
+    sj.pz = m->pz[i & 1];
+    sj.emb = m->emb[i];
+    sj.gamma = m->gamma[i];
+    sj.beta = m->beta[i];
+    sj.w_s = m->w_s;
+    sj.w_e = m->w_e;
+    sj.eps = m->eps;
+    sj.state_out = m->states;
+    sj.state_dbg = (dbg && dbg->stage_state)
+                       ? static_cast<void*>(static_cast<char*>(dbg->stage_state) + (size_t)row_off[i] * D * m->esz)
+                       : nullptr;
+    HIP_TRY(launch_stage(sj, st));
+
+    const int proj_next = i + 1 < n ? i + 1 : -1;
+    if (m->bf16) {
+      spec_status_t s = run_contraction(m, i, proj_next, m->states, false, D, (int)R[i], top_k[i], nullptr,
+                                        m->pz[(i + 1) & 1], &nparts, st);
+      if (s != SPEC_OK) return s;
+    } else {
+      const float* sf = static_cast<const float*>(m->states);
+      HIP_TRY(launch_gemm_f32(sf, D, static_cast<const float*>(m->head[i]), D, m->logits, V, (int)R[i], V, D, st));
+      HIP_TRY(launch_row_topk_f32(m->logits, V, (int)R[i], V, top_k[i], m->part, st));
+      nparts = 1;
+      if (proj_next >= 0)
+        HIP_TRY(launch_gemm_f32(sf, D, static_cast<const float*>(m->proj[proj_next]), D, m->pz[(i + 1) & 1], D,
+                                (int)R[i], D, D, st));
+    }
+  }
+
+  TreeJob tj;
+  memset(&tj, 0, sizeof(tj));
+  tj.batch = batch;
+  tj.n = n;
+  tj.B = B;
+  tj.L = (int)L;
+  for (int i = 0; i < n; ++i) {
+    tj.top_k[i] = top_k[i];
+    tj.off[i] = off[i];
+    tj.row_off[i] = row_off[i];
+  }
+  tj.part = m->part;
+  tj.nparts = nparts;
+  tj.tok = m->tok;
+  tj.logp = m->logp;
+  tj.lse = m->lse;
+  tj.cand_tokens = cand_tokens;
+  tj.cand_scores = cand_scores;
+  tj.cand_leaf = cand_leaf;
+  HIP_TRY(launch_tree(tj, st));
+
+  if (dbg) {
+    const int64_t nk = off[n - 1] + R[n - 1] * top_k[n - 1], nr = row_off[n - 1] + R[n - 1];
+    if (dbg->topk_tok) HIP_TRY(hipMemcpyAsync(dbg->topk_tok, m->tok, (size_t)nk * 4, hipMemcpyDeviceToDevice, st));
+    if (dbg->topk_logp) HIP_TRY(hipMemcpyAsync(dbg->topk_logp, m->logp, (size_t)nk * 4, hipMemcpyDeviceToDevice, st));
+    if (dbg->row_lse) HIP_TRY(hipMemcpyAsync(dbg->row_lse, m->lse, (size_t)nr * 4, hipMemcpyDeviceToDevice, st));
+  }
+  return SPEC_OK;
+}
+
+extern "C" spec_status_t spec_head_logp(spec_model_t* m, int32_t stage, const void* states, int32_t rows, float* logp,
+                                        void* hip_stream) {
+  if (!m) return fail(SPEC_EINVAL, "model is NULL");
+  if (!states || !logp) return fail(SPEC_EINVAL, "a required pointer is NULL");
+  if (stage < 0 || stage >= m->cfg.n_predict) return fail(SPEC_EINVAL, "stage = %d out of range", stage);
+  if (rows < 1 || rows > m->max_rows) return fail(SPEC_ESHAPE, "rows = %d outside [1, %lld]", rows, (long long)m->max_rows);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int D = m->cfg.inner_dim, V = m->cfg.vocab;
+  if (m->bf16) {
+    int nparts = 0;
+    if (skinny_fits(rows, D / 32)) {
+      spec_status_t s = run_contraction(m, stage, -1, states, true, D, rows, 0, logp, nullptr, &nparts, st);
+      if (s != SPEC_OK) return s;
+    } else {
+      // tile the rows into the model's state buffer, then contract with the store epilogue
+      HIP_TRY(launch_pack_bf16(states, m->states, rows, D, false, st));
+      spec_status_t s = run_contraction(m, stage, -1, m->states, false, D, rows, 0, logp, nullptr, &nparts, st);
+      if (s != SPEC_OK) return s;
+    }
+  } else {
+    HIP_TRY(launch_gemm_f32(static_cast<const float*>(states), D, static_cast<const float*>(m->head[stage]), D, logp, V,
+                            rows, V, D, st));
+  }
+  HIP_TRY(launch_row_log_softmax(logp, logp, V, rows, V, st));
+  return SPEC_OK;
+}
+
+extern "C" spec_status_t spec_verify(const void* base_logits, int32_t logits_dtype, const int32_t* cand_tokens,
+                                     int32_t batch, int32_t B, int32_t n_predict, int32_t vocab, int32_t* greedy,
+                                     int32_t* accept_len, int32_t* best_cand, int32_t* out_tokens, int32_t* n_out,
+                                     int32_t* accept_all, void* hip_stream) {
+  if (!base_logits || !cand_tokens || !greedy || !accept_len || !best_cand || !out_tokens || !n_out)
+    return fail(SPEC_EINVAL, "a required pointer is NULL");
+  if (logits_dtype != SPEC_F32 && logits_dtype != SPEC_BF16)
+    return fail(SPEC_EDTYPE, "logits_dtype = %d is neither SPEC_F32 nor SPEC_BF16", logits_dtype);
+  if (batch < 1 || B < 1 || vocab < 1) return fail(SPEC_EINVAL, "batch, B and vocab must be >= 1");
+  if (n_predict < 1 || n_predict > SPEC_MAX_STAGES)
+    return fail(SPEC_EINVAL, "n_predict = %d outside [1, %d]", n_predict, SPEC_MAX_STAGES);
+  const int64_t rows = (int64_t)batch * B * (n_predict + 1);
+  if (rows > 0x7fffffffLL) return fail(SPEC_ESHAPE, "batch * B * (n_predict + 1) is too large");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  HIP_TRY(launch_argmax_rows(base_logits, logits_dtype == SPEC_BF16, rows, vocab, greedy, st));
+  HIP_TRY(launch_accept(greedy, cand_tokens, batch, B, n_predict, accept_len, best_cand, out_tokens, n_out, accept_all,
+                        st));
+  return SPEC_OK;
+}
+
+extern "C" const char* spec_last_error(void) { return g_err; }
+
+extern "C" spec_status_t spec_version(int32_t* major, int32_t* minor) {
+  if (!major || !minor) return fail(SPEC_EINVAL, "major or minor is NULL");
+  *major = 0;
+  *minor = 1;
+  return SPEC_OK;
+}
