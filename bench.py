@@ -1,0 +1,204 @@
+"""Benchmark of one draft + verify step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step = spec_draft followed by spec_verify, enqueued back to back on one
+stream, on one batch of seeded synthetic inputs that are resident in HBM before
+the timed region starts (the base model's forward between the two calls is not
+part of this path; its logits are pre-generated).  Prints ONE JSON line.
+
+Extra objects on the line:
+  roofline      dominant contraction kernel: algorithmic bytes (or flops) per
+                launch / its average launch duration, measured live with HIP
+                events recorded by the library around each launch (on the
+                stream the kernels run on), against the MI355X peak.
+  cpu_baseline  the CPU oracle (as it stands) timed on the host cores on a
+                bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
+KERNEL_NAMES = {0: "head_skinny_kernel", 1: "head_gemm_kernel<2,1>", 2: "head_gemm_kernel<4,1>",
+                3: "head_gemm_kernel<8,4>"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama7b_b1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding in "
+              "this path)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2404_19124_amd import binding as B
+    from paper_2404_19124_amd import workloads as W
+    from paper_2404_19124_amd.runner import Step
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    wl = W.WORKLOADS[args.workload]
+    gen = W.make_generator(wl.seed, "cuda")
+    w = W.make_speculator(wl, gen, device="cuda")
+    state, last = W.make_draft_inputs(wl, gen, device="cuda")
+    step = Step(wl, w)
+    stream = torch.cuda.current_stream()
+
+    # inputs of verify: logits boosted at the candidates this draft produces
+    step.draft(state, last)
+    torch.cuda.synchronize()
+    logits = W.make_base_logits(wl, step.cand_tokens, gen, device="cuda")
+    torch.cuda.synchronize()
+
+    def one_step():
+        step.draft(state, last, stream)
+        step.verify(logits, None, stream)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    steps_per_s = args.steps / dt
+    mean_accept = float(step.accept_len.float().mean())
+
+    # ---- dominant kernel, timed live with events around each launch
+    B.spec_profile_enable(step.model, 16 * args.steps)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    ms_per_step_events = (time.perf_counter() - t1) * 1e3 / args.steps
+    recs = B.spec_profile_read(step.model, 16 * args.steps)
+    B.spec_profile_enable(step.model, 0)
+    by_kernel = {}
+    for r in recs:
+        d = by_kernel.setdefault(r["kernel"], {"ms": 0.0, "n": 0, "bytes": 0.0, "flops": 0.0})
+        d["ms"] += r["ms"]
+        d["n"] += 1
+        # algorithmic traffic of a launch: the weights once, the state rows once
+        d["bytes"] += 2.0 * r["weight_rows"] * r["k"] + 2.0 * r["rows"] * r["k"]
+        d["flops"] += 2.0 * r["rows"] * r["weight_rows"] * r["k"]
+    dom = max(by_kernel, key=lambda k: by_kernel[k]["ms"])
+    d = by_kernel[dom]
+    avg_ms = d["ms"] / d["n"]
+    gbs = d["bytes"] / d["n"] / (avg_ms * 1e-3) / 1e9
+    tflops = d["flops"] / d["n"] / (avg_ms * 1e-3) / 1e12
+    # which roof binds this kernel: compare the two ideal times
+    t_hbm = d["bytes"] / d["n"] / (HBM_PEAK_GBS * 1e9)
+    t_mfma = d["flops"] / d["n"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    traffic = _traffic_from_profiles(args.workload, KERNEL_NAMES[dom])
+    if t_hbm >= t_mfma:
+        roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic}
+    else:
+        roofline = {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic}
+    roofline.update({"kernel": KERNEL_NAMES[dom], "avg_launch_us": round(avg_ms * 1e3, 2),
+                     "launches_per_step": d["n"] / args.steps,
+                     "algorithmic_bytes_per_launch": d["bytes"] / d["n"],
+                     "flops_per_launch": d["flops"] / d["n"],
+                     "gbs": round(gbs, 1), "tflops": round(tflops, 2),
+                     "ms_per_step_with_events": round(ms_per_step_events, 4),
+                     "share_of_step": round(d["ms"] / args.steps / ms_per_step_events, 3)})
+
+    ab = wl.algorithmic_bytes()
+    out = {
+        "metric": "draft+verify steps/s", "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.weight_dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "batch": wl.batch, "emb_dim": wl.emb_dim, "inner_dim": wl.inner_dim,
+                   "vocab": wl.vocab, "n_predict": wl.n_predict, "top_k": list(wl.top_k), "B": wl.B,
+                   "logits_dtype": wl.logits_dtype, "seed": wl.seed},
+        "step_algorithmic_bytes": ab["total"],
+        "step_hbm_gbs": round(ab["total"] / (ms_per_step * 1e-3) / 1e9, 1),
+        "step_hbm_frac": round(ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "step_contraction_tflops": round(wl.contraction_flops() / (ms_per_step * 1e-3) / 1e12, 2),
+        "mean_accept_len_synthetic": round(mean_accept, 3),
+        "roofline": roofline,
+    }
+    out["cpu_baseline"] = None if args.no_cpu_baseline else _cpu_baseline(wl, w, state, last, logits, step,
+                                                                          args.cpu_seconds)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def _traffic_from_profiles(workload: str, kernel: str):
+    """HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc
+    (FETCH_SIZE, WRITE_SIZE) and kept as text under profiles/; None when no such
+    measurement has been recorded for this workload."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            table = json.load(f)
+        return table.get(workload, {}).get(kernel)
+    except (OSError, ValueError):
+        return None
+
+
+def _cpu_baseline(wl, w, state, last, logits, step, budget_s: float):
+    """The oracle timed on the host: whole steps on a bounded number of sequences."""
+    import numpy as np
+    import torch
+    from oracle import spec_oracle as O
+    from paper_2404_19124_amd import workloads as W
+
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    threads = torch.get_num_threads()
+    wn = W.weights_to_numpy(w)
+    nseq = min(wl.batch, 2)
+    st = W.to_numpy_f32(state[:nseq])
+    lt = last[:nseq].cpu().numpy()
+    lg = W.to_numpy_f32(logits[:nseq])
+    cand = step.cand_tokens[:nseq].cpu().numpy()
+    # one untimed call sizes the sample
+    t0 = time.perf_counter()
+    O.draft(wn, st[:1], lt[:1], wl.top_k, wl.B, state_dtype=wl.weight_dtype)
+    O.verify(lg[:1], cand[:1])
+    per_seq = time.perf_counter() - t0
+    nseq = 1 if per_seq * 2 > budget_s or wl.batch == 1 else nseq
+    reps = max(1, min(5, int(budget_s / max(per_seq * nseq, 1e-3))))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        d = O.draft(wn, st[:nseq], lt[:nseq], wl.top_k, wl.B, state_dtype=wl.weight_dtype)
+        O.verify(lg[:nseq], d.cand_tokens)
+    dt = (time.perf_counter() - t0) / reps
+    # a step covers the whole batch: scale the sampled sequences up (sequences are independent)
+    step_s = dt * wl.batch / nseq
+    return {"value": round(1.0 / step_s, 4), "unit": "steps/s", "cores": cores, "kind": "oracle",
+            "blas_threads": threads,
+            "sample": "%d whole draft+verify step(s) of %d of %d sequence(s), %d repetition(s), %.2f s each; "
+                      "scaled by batch/sample" % (reps, nseq, wl.batch, reps, dt)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

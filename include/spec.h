@@ -154,6 +154,26 @@ spec_status_t spec_verify(const void* base_logits, int32_t logits_dtype, const i
 spec_status_t spec_head_logp(spec_model_t* m, int32_t stage, const void* states, int32_t rows,
                              float* logp, void* hip_stream);
 
+/* Live timing of the contraction launches (the kernels that bound the step), for
+ * roofline reports.  While enabled, spec_draft records a HIP event before and
+ * after every contraction launch on the caller's stream; nothing else changes.
+ *   kernel: 0 = rows<=16 streaming kernel, 1..3 = dense kernel with 32/64/128-row tiles
+ *   rows, weight_rows, k: the contraction is [rows, k] x [weight_rows, k]^T
+ *                  (weight_rows counts head and fused next-projection rows together)
+ *   ms: elapsed time between the two events */
+typedef struct {
+  int32_t kernel, rows, weight_rows, k;
+  float ms;
+} spec_launch_record_t;
+
+/* capacity > 0: start recording up to `capacity` launches (older records are dropped when
+ * full); capacity == 0: stop and release the events. */
+spec_status_t spec_profile_enable(spec_model_t* m, int32_t capacity);
+
+/* Waits for the recorded events, writes up to `cap` records to `out` (host) in launch
+ * order, stores their number in *n (host) and clears the recording. */
+spec_status_t spec_profile_read(spec_model_t* m, spec_launch_record_t* out, int32_t cap, int32_t* n);
+
 /* Reads back the mix weights and epsilon the model uses (after defaults were applied). */
 spec_status_t spec_model_scalars(const spec_model_t* m, float* state_weight, float* emb_weight,
                                  float* ln_eps);

@@ -22,7 +22,7 @@ SPEC_OK, SPEC_EINVAL, SPEC_ESHAPE, SPEC_EDTYPE, SPEC_ENOMEM, SPEC_EHIP = 0, -1, 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecdraft.so")
 
 EXPORTS = ["spec_create", "spec_destroy", "spec_draft", "spec_verify", "spec_head_logp", "spec_model_scalars",
-           "spec_last_error", "spec_version"]
+           "spec_profile_enable", "spec_profile_read", "spec_last_error", "spec_version"]
 
 
 class SpecError(RuntimeError):
@@ -45,6 +45,11 @@ class spec_weights_t(C.Structure):
 class spec_debug_t(C.Structure):
     _fields_ = [("stage_state", C.c_void_p), ("topk_tok", C.c_void_p), ("topk_logp", C.c_void_p),
                 ("row_lse", C.c_void_p)]
+
+
+class spec_launch_record_t(C.Structure):
+    _fields_ = [("kernel", C.c_int32), ("rows", C.c_int32), ("weight_rows", C.c_int32), ("k", C.c_int32),
+                ("ms", C.c_float)]
 
 
 _lib = None
@@ -73,6 +78,10 @@ def lib() -> C.CDLL:
         l.spec_head_logp.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         l.spec_model_scalars.restype = C.c_int
         l.spec_model_scalars.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float)]
+        l.spec_profile_enable.restype = C.c_int
+        l.spec_profile_enable.argtypes = [C.c_void_p, C.c_int32]
+        l.spec_profile_read.restype = C.c_int
+        l.spec_profile_read.argtypes = [C.c_void_p, C.POINTER(spec_launch_record_t), C.c_int32, C.POINTER(C.c_int32)]
         l.spec_last_error.restype = C.c_char_p
         l.spec_last_error.argtypes = []
         l.spec_version.restype = C.c_int
@@ -185,6 +194,18 @@ def spec_verify(base_logits: torch.Tensor, cand_tokens: torch.Tensor, greedy: to
     _check(lib().spec_verify(_ptr(base_logits), code, _ptr(cand_tokens), b, B, n1 - 1, V, _ptr(greedy),
                              _ptr(accept_len), _ptr(best_cand), _ptr(out_tokens), _ptr(n_out), _ptr(accept_all),
                              _stream_ptr(stream)))
+
+
+def spec_profile_enable(model: SpecModel, capacity: int) -> None:
+    _check(lib().spec_profile_enable(model.handle, int(capacity)))
+
+
+def spec_profile_read(model: SpecModel, cap: int = 65536):
+    """Returns a list of dicts (kernel, rows, weight_rows, k, ms), in launch order."""
+    buf = (spec_launch_record_t * cap)()
+    n = C.c_int32()
+    _check(lib().spec_profile_read(model.handle, buf, cap, C.byref(n)))
+    return [dict(kernel=r.kernel, rows=r.rows, weight_rows=r.weight_rows, k=r.k, ms=r.ms) for r in buf[:n.value]]
 
 
 def spec_head_logp(model: SpecModel, stage: int, states: torch.Tensor, logp: torch.Tensor, stream=None) -> None:

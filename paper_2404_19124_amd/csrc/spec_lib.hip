@@ -66,10 +66,16 @@ struct spec_model {
   float* logits;             // f32 path and spec_head_logp: materialised rows
   int64_t logits_rows;
   std::vector<void*> owned;
+  // live timing of contraction launches
+  struct Rec { int kernel, rows, weight_rows, k; };
+  std::vector<hipEvent_t> ev;   // 2 per record slot
+  std::vector<Rec> rec;
+  int prof_cap = 0, prof_n = 0;
 };
 
 static void free_model(spec_model* m) {
   if (!m) return;
+  for (hipEvent_t e : m->ev) (void)hipEventDestroy(e);
   for (void* p : m->owned)
     if (p) (void)hipFree(p);
   delete m;
@@ -253,6 +259,54 @@ extern "C" spec_status_t spec_model_scalars(const spec_model_t* m, float* state_
   return SPEC_OK;
 }
 
+static int prof_begin(spec_model* m, int kernel, int rows, int weight_rows, int k, hipStream_t st) {
+  if (m->prof_cap <= 0 || m->prof_n >= m->prof_cap) return -1;
+  const int slot = m->prof_n++;
+  m->rec[slot] = {kernel, rows, weight_rows, k};
+  (void)hipEventRecord(m->ev[2 * slot], st);
+  return slot;
+}
+static void prof_end(spec_model* m, int slot, hipStream_t st) {
+  if (slot >= 0) (void)hipEventRecord(m->ev[2 * slot + 1], st);
+}
+
+extern "C" spec_status_t spec_profile_enable(spec_model_t* m, int32_t capacity) {
+  if (!m) return fail(SPEC_EINVAL, "model is NULL");
+  if (capacity < 0 || capacity > (1 << 20)) return fail(SPEC_EINVAL, "capacity = %d out of range", capacity);
+  for (hipEvent_t e : m->ev) (void)hipEventDestroy(e);
+  m->ev.clear();
+  m->rec.clear();
+  m->prof_cap = 0;
+  m->prof_n = 0;
+  for (int i = 0; i < 2 * capacity; ++i) {
+    hipEvent_t e;
+    HIP_TRY(hipEventCreate(&e));
+    m->ev.push_back(e);
+  }
+  m->rec.resize(capacity);
+  m->prof_cap = capacity;
+  return SPEC_OK;
+}
+
+extern "C" spec_status_t spec_profile_read(spec_model_t* m, spec_launch_record_t* out, int32_t cap, int32_t* n) {
+  if (!m || !out || !n) return fail(SPEC_EINVAL, "a required pointer is NULL");
+  int w = 0;
+  for (int i = 0; i < m->prof_n && w < cap; ++i) {
+    HIP_TRY(hipEventSynchronize(m->ev[2 * i + 1]));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, m->ev[2 * i], m->ev[2 * i + 1]));
+    out[w].kernel = m->rec[i].kernel;
+    out[w].rows = m->rec[i].rows;
+    out[w].weight_rows = m->rec[i].weight_rows;
+    out[w].k = m->rec[i].k;
+    out[w].ms = ms;
+    ++w;
+  }
+  *n = w;
+  m->prof_n = 0;
+  return SPEC_OK;
+}
+
 // One contraction of R state rows against head[stage] (top-k partials, or raw
 // logits into out_head) and, if proj_stage >= 0, against proj[proj_stage]
 // (stored to out_proj).  Returns the number of parts per row it produced.
@@ -287,7 +341,9 @@ static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, c
   if (skinny_fits(R, job.kt)) {
     job.nparts = skinny_grid(m->n_cu);
     *nparts = job.nparts;
+    const int slot = prof_begin(m, 0, R, job.n_head + job.n_proj, K, st);
     HIP_TRY(launch_head_skinny(job, m->n_cu, st));
+    prof_end(m, slot, st);
     return SPEC_OK;
   }
   // general path wants tiled states
@@ -303,11 +359,15 @@ static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, c
     *nparts = pl.n_tiles;
     if (!out_head && (int64_t)R * pl.n_tiles > m->part_rows_parts)
       return fail(SPEC_ESHAPE, "internal: partial workspace too small (%d rows x %d parts)", R, pl.n_tiles);
+    const int slot = prof_begin(m, pl.mi == 2 ? 1 : (pl.mi == 4 ? 2 : 3), R, job.n_head, K, st);
     HIP_TRY(launch_head_gemm(job, false, pl, st));
+    prof_end(m, slot, st);
   }
   if (proj_stage >= 0) {
     GemmPlan pl = plan_gemm(R, D);
+    const int slot = prof_begin(m, pl.mi == 2 ? 1 : (pl.mi == 4 ? 2 : 3), R, job.n_proj, K, st);
     HIP_TRY(launch_head_gemm(job, true, pl, st));
+    prof_end(m, slot, st);
   }
   return SPEC_OK;
 }
