@@ -155,8 +155,9 @@ spec_status_t spec_head_logp(spec_model_t* m, int32_t stage, const void* states,
                              float* logp, void* hip_stream);
 
 /* Live timing of the contraction launches (the kernels that bound the step), for
- * roofline reports.  While enabled, spec_draft records a HIP event before and
- * after every contraction launch on the caller's stream; nothing else changes.
+ * roofline reports.  While enabled, spec_draft attaches a pair of HIP events to
+ * every contraction launch (they receive that kernel's begin / end time on the
+ * caller's stream); nothing else changes.
  *   kernel: 0 = rows<=16 streaming kernel, 1..3 = dense kernel with 32/64/128-row tiles
  *   rows, weight_rows, k: the contraction is [rows, k] x [weight_rows, k]^T
  *                  (weight_rows counts head and fused next-projection rows together)
@@ -166,8 +167,8 @@ typedef struct {
   float ms;
 } spec_launch_record_t;
 
-/* capacity > 0: start recording up to `capacity` launches (older records are dropped when
- * full); capacity == 0: stop and release the events. */
+/* capacity > 0: start recording up to `capacity` launches (further launches are not
+ * recorded once full, until spec_profile_read empties the recording); capacity == 0: stop and release the events. */
 spec_status_t spec_profile_enable(spec_model_t* m, int32_t capacity);
 
 /* Waits for the recorded events, writes up to `cap` records to `out` (host) in launch

@@ -24,24 +24,76 @@ __device__ __forceinline__ bool before(float v1, int32_t i1, float v2, int32_t i
   return (v1 > v2) || (v1 == v2 && i1 < i2);
 }
 
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+// ---- wave reductions ---------------------------------------------------------
+// Within a row of 16 lanes the exchange runs on DPP (quad permutes, then the
+// half-row and row mirrors): four steps of a few cycles each instead of LDS
+// crossbar shuffles.  The four row results are then read with v_readlane and
+// combined uniformly, so every lane ends with the result.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+template <int CTRL>
+__device__ __forceinline__ int32_t dpp_i(int32_t x) {
+  return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, false);
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each 8
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each 16
+__device__ __forceinline__ float lane_f(float x, int l) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
+}
+
+__device__ __forceinline__ float row16_sum(float x) {
+  x += dpp_f<kDppXor1>(x);
+  x += dpp_f<kDppXor2>(x);
+  x += dpp_f<kDppHalfMirror>(x);
+  x += dpp_f<kDppMirror>(x);
   return x;
 }
-__device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+__device__ __forceinline__ float row16_max(float x) {
+  x = fmaxf(x, dpp_f<kDppXor1>(x));
+  x = fmaxf(x, dpp_f<kDppXor2>(x));
+  x = fmaxf(x, dpp_f<kDppHalfMirror>(x));
+  x = fmaxf(x, dpp_f<kDppMirror>(x));
   return x;
+}
+template <int CTRL>
+__device__ __forceinline__ void best_step(float& v, int32_t& i) {
+  const float ov = dpp_f<CTRL>(v);
+  const int32_t oi = dpp_i<CTRL>(i);
+  if (before(ov, oi, v, i)) { v = ov; i = oi; }
+}
+// best (value, index) over each row of 16 lanes
+__device__ __forceinline__ void row16_best(float& v, int32_t& i) {
+  best_step<kDppXor1>(v, i);
+  best_step<kDppXor2>(v, i);
+  best_step<kDppHalfMirror>(v, i);
+  best_step<kDppMirror>(v, i);
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+  x = row16_sum(x);
+  return (lane_f(x, 0) + lane_f(x, 16)) + (lane_f(x, 32) + lane_f(x, 48));
+}
+__device__ __forceinline__ float wave_max(float x) {
+  x = row16_max(x);
+  return fmaxf(fmaxf(lane_f(x, 0), lane_f(x, 16)), fmaxf(lane_f(x, 32), lane_f(x, 48)));
 }
 // best (value, index) over the wave; every lane gets the result
 __device__ __forceinline__ void wave_best(float& v, int32_t& i) {
+  row16_best(v, i);
+  float bv = lane_f(v, 0);
+  int32_t bi = __builtin_amdgcn_readlane(i, 0);
 #pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) {
-    float ov = __shfl_xor(v, o, 64);
-    int32_t oi = __shfl_xor(i, o, 64);
-    if (before(ov, oi, v, i)) { v = ov; i = oi; }
+  for (int r = 16; r < 64; r += 16) {
+    const float ov = lane_f(v, r);
+    const int32_t oi = __builtin_amdgcn_readlane(i, r);
+    if (before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
   }
+  v = bv;
+  i = bi;
 }
 
 // Block-wide helpers for blocks of NT threads (NT multiple of 64, <= 1024).

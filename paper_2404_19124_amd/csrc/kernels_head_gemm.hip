@@ -18,6 +18,8 @@
 //  * workgroup ids are remapped so that the tiles of one XCD (ids congruent
 //    mod 8) walk a contiguous range of weight-row tiles with the state-row tile
 //    varying fastest: workgroups that share weights run together on one L2.
+#include <hip/hip_ext.h>
+
 #include "device_utils.h"
 #include "spec_internal.h"
 
@@ -270,7 +272,8 @@ static size_t gemm_smem(int mi) {
   return slabs > epi ? slabs : epi;
 }
 
-hipError_t launch_head_gemm(const HeadJob& job, bool proj_matrix, const GemmPlan& pl, hipStream_t st) {
+hipError_t launch_head_gemm(const HeadJob& job, bool proj_matrix, const GemmPlan& pl, hipStream_t st,
+                            hipEvent_t ev_start, hipEvent_t ev_stop) {
   GemmArgs a;
   a.w = static_cast<const uint4*>(proj_matrix ? job.w_proj : job.w_head);
   a.nt_total = proj_matrix ? job.vt_proj : job.vt_head;
@@ -301,9 +304,9 @@ hipError_t launch_head_gemm(const HeadJob& job, bool proj_matrix, const GemmPlan
   a.nparts = job.nparts;
   dim3 grid(a.chunk * 8), block(256);
   const size_t smem = gemm_smem(pl.mi);
-  if (pl.mi == 2 && pl.ni == 1) hipLaunchKernelGGL((head_gemm_kernel<2, 1>), grid, block, smem, st, a);
-  else if (pl.mi == 4 && pl.ni == 1) hipLaunchKernelGGL((head_gemm_kernel<4, 1>), grid, block, smem, st, a);
-  else if (pl.mi == 8 && pl.ni == 4) hipLaunchKernelGGL((head_gemm_kernel<8, 4>), grid, block, smem, st, a);
+  if (pl.mi == 2 && pl.ni == 1) hipExtLaunchKernelGGL((head_gemm_kernel<2, 1>), grid, block, smem, st, ev_start, ev_stop, 0, a);
+  else if (pl.mi == 4 && pl.ni == 1) hipExtLaunchKernelGGL((head_gemm_kernel<4, 1>), grid, block, smem, st, ev_start, ev_stop, 0, a);
+  else if (pl.mi == 8 && pl.ni == 4) hipExtLaunchKernelGGL((head_gemm_kernel<8, 4>), grid, block, smem, st, ev_start, ev_stop, 0, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -9,8 +9,9 @@
 //    [head tiles | next projection's tiles] (both consume the same states);
 //  * K is split over the 16 waves; each wave streams its slice of the tile from
 //    the tiled weight layout as fully coalesced 1 KiB fragments straight into
-//    registers, one tile ahead of the matrix-core work (the loads of tile i+1 are
-//    issued as the registers of tile i are consumed);
+//    registers, DEPTH tiles ahead of the matrix-core work (a register ring of
+//    DEPTH x NS fragments per wave: the loads of tile i+DEPTH are issued as the
+//    registers of tile i are consumed);
 //  * the states (<= 16 rows x K) sit in LDS for the whole kernel and feed the B
 //    operand of v_mfma_f32_16x16x32_bf16; the A operand is the weight fragment,
 //    so an accumulator lane holds 4 vocabulary entries of one state row;
@@ -18,6 +19,8 @@
 //    barrier per tile) by 256 threads, which keep per-thread running
 //    (max, sum-exp, top-k) for "their" vocabulary residue; logits never leave
 //    the CU.  At the end the workgroup writes one partial per row.
+#include <hip/hip_ext.h>
+
 #include "device_utils.h"
 #include "spec_internal.h"
 
@@ -35,6 +38,10 @@ bool skinny_fits(int R, int kt) {
 }
 int skinny_grid(int n_cu) { return n_cu > 0 ? n_cu : 256; }
 
+// NS = K-steps per wave held per tile, DEPTH = tiles in flight per wave.
+// EXACT: every wave has exactly NS steps (K = 16 * 32 * NS); otherwise waves
+// take ceil(kt/16) <= NS steps with the tail predicated off.
+template <int NS, int DEPTH, bool EXACT>
 __global__ __launch_bounds__(kSkinnyWaves * 64) void head_skinny_kernel(HeadJob p) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int kt = p.kt, R = p.R;
@@ -43,6 +50,34 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void head_skinny_kernel(HeadJob 
   f32x4* ldsP = reinterpret_cast<f32x4*>(smem + bytesB);  // [2][waves][64]
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   constexpr int NT = kSkinnyWaves * 64;
+
+  // ---- this wave's slice of K; the first tile's weights are requested before
+  // anything else so that the stream is already in flight while the states load
+  const int spw = EXACT ? NS : (kt + kSkinnyWaves - 1) / kSkinnyWaves;
+  const int s0 = min(w * spw, kt);
+  const int ns = EXACT ? NS : min(kt, s0 + spw) - s0;
+  const int g = lane >> 4, nn = min(lane & 15, R - 1);
+  const uint4* bptr = ldsB + ((int64_t)s0 * 4 + g) * R + nn;  // step t: + t*4*R
+  const int total = p.vt_head + p.vt_proj;
+  const uint4* wh = static_cast<const uint4*>(p.w_head);
+  const uint4* wp = static_cast<const uint4*>(p.w_proj);
+  auto tile_ptr = [&](int tile) -> const uint4* {
+    const uint4* base = tile < p.vt_head ? wh + (int64_t)tile * kt * 64 : wp + (int64_t)(tile - p.vt_head) * kt * 64;
+    return base + (int64_t)s0 * 64 + lane;
+  };
+
+  const int G = gridDim.x;
+  uint4 a[DEPTH][NS];
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d) {
+    const int tile = blockIdx.x + d * G;
+    if (tile < total) {
+      const uint4* ptr = tile_ptr(tile);
+#pragma unroll
+      for (int t = 0; t < NS; ++t)
+        if (EXACT || t < ns) a[d][t] = ptr[t * 64];
+    }
+  }
 
   // ---- states -> LDS, trimmed to R rows: slot (t, g, n) = row n, columns t*32 + g*8 .. +8
   for (int slot = tid; slot < kt * 4 * R; slot += NT) {
@@ -56,29 +91,6 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void head_skinny_kernel(HeadJob 
   }
   __syncthreads();
 
-  // ---- this wave's slice of K
-  const int spw = (kt + kSkinnyWaves - 1) / kSkinnyWaves;
-  const int s0 = min(w * spw, kt);
-  const int ns = min(kt, s0 + spw) - s0;
-  const int g = lane >> 4, nn = min(lane & 15, R - 1);
-  const uint4* bptr = ldsB + ((int64_t)s0 * 4 + g) * R + nn;  // step t: + t*4*R
-  const int total = p.vt_head + p.vt_proj;
-  const uint4* wh = static_cast<const uint4*>(p.w_head);
-  const uint4* wp = static_cast<const uint4*>(p.w_proj);
-  auto tile_ptr = [&](int tile) -> const uint4* {
-    const uint4* base = tile < p.vt_head ? wh + (int64_t)tile * kt * 64 : wp + (int64_t)(tile - p.vt_head) * kt * 64;
-    return base + (int64_t)s0 * 64 + lane;
-  };
-
-  int tile = blockIdx.x;
-  uint4 a[kSkinnySteps];
-  if (tile < total) {
-    const uint4* ptr = tile_ptr(tile);
-#pragma unroll
-    for (int t = 0; t < kSkinnySteps; ++t)
-      if (t < ns) a[t] = ptr[t * 64];
-  }
-
   // running state of the 256 epilogue threads: state row en, vocabulary residue vi
   const int en = tid & 15, vi = (tid >> 4) & 15;
   float run_m = SPEC_NEG_INF, run_s = 0.f;
@@ -88,62 +100,68 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void head_skinny_kernel(HeadJob 
   for (int q = 0; q < kMaxTopK; ++q) { tv[q] = SPEC_NEG_INF; ti[q] = kIdxNone; }
 
   int buf = 0;
-  for (; tile < total; tile += gridDim.x) {
-    const int next = tile + gridDim.x;
-    const bool has_next = next < total;
-    const uint4* nptr = tile_ptr(has_next ? next : tile);
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int base = blockIdx.x; base < total; base += DEPTH * G) {
 #pragma unroll
-    for (int t = 0; t < kSkinnySteps; ++t) {
-      if (t < ns) {
-        const uint4 b = bptr[(int64_t)t * 4 * R];
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[t]),
-                                                      __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
-        if (has_next) a[t] = nptr[t * 64];
-      }
-    }
-    ldsP[(buf * kSkinnyWaves + w) * 64 + lane] = acc;
-    __syncthreads();
-    if (tid < 256) {
-      // accumulator lane l holds state row l%16 and weight rows (l/16)*4 + i
-      const float* P = reinterpret_cast<const float*>(ldsP + buf * kSkinnyWaves * 64);
-      const int l = (vi >> 2) * 16 + en, i = vi & 3;
-      float sum = 0.f;
+    for (int d = 0; d < DEPTH; ++d) {
+      const int tile = base + d * G;
+      if (tile < total) {
+        const int next = tile + DEPTH * G;
+        const bool has_next = next < total;
+        const uint4* nptr = tile_ptr(has_next ? next : tile);
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ww = 0; ww < kSkinnyWaves; ++ww) sum += P[(ww * 64 + l) * 4 + i];
-      if (en < R) {
-        if (tile < p.vt_head) {
-          const int v = tile * 16 + vi;
-          if (v < p.n_head) {
-            if (p.out_head) {
-              p.out_head[(int64_t)en * p.ld_head + v] = sum;
-            } else {
-              const float m_new = fmaxf(run_m, sum);
-              run_s = run_s * __expf(run_m - m_new) + __expf(sum - m_new);
-              run_m = m_new;
-              if (sum > tv[kMaxTopK - 1]) {
-                float cv = sum;
-                int32_t ci = v;
+        for (int t = 0; t < NS; ++t) {
+          if (EXACT || t < ns) {
+            const uint4 b = bptr[(int64_t)t * 4 * R];
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[d][t]),
+                                                          __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+            if (has_next) a[d][t] = nptr[t * 64];
+          }
+        }
+        ldsP[(buf * kSkinnyWaves + w) * 64 + lane] = acc;
+        __syncthreads();
+        if (tid < 256) {
+          // accumulator lane l holds state row l%16 and weight rows (l/16)*4 + i
+          const float* P = reinterpret_cast<const float*>(ldsP + buf * kSkinnyWaves * 64);
+          const int l = (vi >> 2) * 16 + en, i = vi & 3;
+          float sum = 0.f;
 #pragma unroll
-                for (int q = 0; q < kMaxTopK; ++q) {
-                  const bool gt = cv > tv[q];
-                  const float ov = tv[q];
-                  const int32_t oi = ti[q];
-                  tv[q] = gt ? cv : ov;
-                  ti[q] = gt ? ci : oi;
-                  cv = gt ? ov : cv;
-                  ci = gt ? oi : ci;
+          for (int ww = 0; ww < kSkinnyWaves; ++ww) sum += P[(ww * 64 + l) * 4 + i];
+          if (en < R) {
+            if (tile < p.vt_head) {
+              const int v = tile * 16 + vi;
+              if (v < p.n_head) {
+                if (p.out_head) {
+                  p.out_head[(int64_t)en * p.ld_head + v] = sum;
+                } else {
+                  const float m_new = fmaxf(run_m, sum);
+                  run_s = run_s * __expf(run_m - m_new) + __expf(sum - m_new);
+                  run_m = m_new;
+                  if (sum > tv[kMaxTopK - 1]) {
+                    float cv = sum;
+                    int32_t ci = v;
+#pragma unroll
+                    for (int q = 0; q < kMaxTopK; ++q) {
+                      const bool gt = cv > tv[q];
+                      const float ov = tv[q];
+                      const int32_t oi = ti[q];
+                      tv[q] = gt ? cv : ov;
+                      ti[q] = gt ? ci : oi;
+                      cv = gt ? ov : cv;
+                      ci = gt ? oi : ci;
+                    }
+                  }
                 }
               }
+            } else {
+              const int d2 = (tile - p.vt_head) * 16 + vi;
+              if (d2 < p.n_proj) p.out_proj[(int64_t)en * p.ld_proj + d2] = sum;
             }
           }
-        } else {
-          const int d = (tile - p.vt_head) * 16 + vi;
-          if (d < p.n_proj) p.out_proj[(int64_t)en * p.ld_proj + d] = sum;
         }
+        buf ^= 1;
       }
     }
-    buf ^= 1;
   }
 
   if (p.out_head || p.vt_head == 0) return;
@@ -175,12 +193,8 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void head_skinny_kernel(HeadJob 
       hi[q] = li[(row * 16 + src) * kMaxTopK + q];
     }
     float m = lm[row * 16 + src], s = ls[row * 16 + src];
-    float mx = m;
-#pragma unroll
-    for (int o = 8; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-    s = (m > SPEC_NEG_INF) ? s * __expf(m - mx) : 0.f;
-#pragma unroll
-    for (int o = 8; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+    const float mx = row16_max(m);
+    s = row16_sum((m > SPEC_NEG_INF) ? s * __expf(m - mx) : 0.f);
     const int64_t slot = (int64_t)row * p.nparts + blockIdx.x;
     if (row < R && src == 0) {
       p.part.m[slot] = mx;
@@ -191,12 +205,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void head_skinny_kernel(HeadJob 
       if (j < p.k_top) {
         float bv = hv[0];
         int32_t bi = hi[0];
-#pragma unroll
-        for (int o = 8; o >= 1; o >>= 1) {
-          const float ov = __shfl_xor(bv, o, 64);
-          const int32_t oi = __shfl_xor(bi, o, 64);
-          if (before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-        }
+        row16_best(bv, bi);
         if (hi[0] == bi && hv[0] == bv) {  // the owner of the winner pops it
 #pragma unroll
           for (int q = 0; q + 1 < kMaxTopK; ++q) { hv[q] = hv[q + 1]; hi[q] = hi[q + 1]; }
@@ -212,18 +221,34 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void head_skinny_kernel(HeadJob 
   }
 }
 
-hipError_t launch_head_skinny(const HeadJob& job, int n_cu, hipStream_t st) {
-  const size_t bytesB = ((size_t)job.kt * 4 * job.R * 16 + 255) & ~(size_t)255;
-  const size_t smem = bytesB + kSkinnyLdsP;
-  static bool attr_set = false;
+template <int NS, int DEPTH, bool EXACT>
+static hipError_t launch_skinny_t(const HeadJob& job, int grid, size_t smem, hipStream_t st, hipEvent_t ev_start,
+                                  hipEvent_t ev_stop) {
+  static bool attr_set = false;  // per instantiation
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_skinny_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_skinny_kernel<NS, DEPTH, EXACT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kSkinnyLdsB + kSkinnyLdsP));
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(head_skinny_kernel, dim3(skinny_grid(n_cu)), dim3(kSkinnyWaves * 64), smem, st, job);
+  hipExtLaunchKernelGGL((head_skinny_kernel<NS, DEPTH, EXACT>), dim3(grid), dim3(kSkinnyWaves * 64), smem, st,
+                        ev_start, ev_stop, 0, job);
   return hipGetLastError();
+}
+
+hipError_t launch_head_skinny(const HeadJob& job, int n_cu, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
+  const size_t bytesB = ((size_t)job.kt * 4 * job.R * 16 + 255) & ~(size_t)255;
+  const size_t smem = bytesB + kSkinnyLdsP;
+  const int grid = skinny_grid(n_cu);
+  // K = 512 * NS gets an exact instantiation with as many tiles in flight as 16 fragments allow
+  switch (job.kt % kSkinnyWaves == 0 ? job.kt / kSkinnyWaves : 0) {
+    case 4: return launch_skinny_t<4, 4, true>(job, grid, smem, st, ev_start, ev_stop);
+    case 6: return launch_skinny_t<6, 2, true>(job, grid, smem, st, ev_start, ev_stop);
+    case 8: return launch_skinny_t<8, 2, true>(job, grid, smem, st, ev_start, ev_stop);
+    case 10: return launch_skinny_t<10, 1, true>(job, grid, smem, st, ev_start, ev_stop);
+    case 16: return launch_skinny_t<16, 1, true>(job, grid, smem, st, ev_start, ev_stop);
+    default: return launch_skinny_t<kSkinnySteps, 1, false>(job, grid, smem, st, ev_start, ev_stop);
+  }
 }
 
 }  // namespace specdraft

@@ -8,15 +8,37 @@
 
 namespace specdraft {
 
-template <bool BF16>
+// NCH = 8-element chunks per thread held in registers (D <= NCH * 2048).
+template <bool BF16, int NCH>
 __global__ __launch_bounds__(256) void stage_kernel(StageJob j) {
-  extern __shared__ float smem[];
-  float* z = smem;              // [D]
-  float* scratch = smem + j.D;  // [8]
+  __shared__ float scratch[8];
   const int tid = threadIdx.x, lane = tid & 63;
   const int r = blockIdx.x;
   const int parent = r / j.k_prev, rank = r - parent * j.k_prev;
-  const int D = j.D;
+  const int D = j.D, nchunk = D / 8;
+
+  // everything that does not depend on the token is requested first: the
+  // projected parent state and the LayerNorm affine
+  const float* pz = j.pz + (int64_t)parent * D;
+  float z[NCH][8], ga[NCH][8], be[NCH][8];
+#pragma unroll
+  for (int ci = 0; ci < NCH; ++ci) {
+    const int c = tid + ci * 256;
+    if (c < nchunk) {
+      const float4 p0 = *reinterpret_cast<const float4*>(pz + c * 8);
+      const float4 p1 = *reinterpret_cast<const float4*>(pz + c * 8 + 4);
+      const float4 g0 = *reinterpret_cast<const float4*>(j.gamma + c * 8);
+      const float4 g1 = *reinterpret_cast<const float4*>(j.gamma + c * 8 + 4);
+      const float4 b0 = *reinterpret_cast<const float4*>(j.beta + c * 8);
+      const float4 b1 = *reinterpret_cast<const float4*>(j.beta + c * 8 + 4);
+      z[ci][0] = p0.x; z[ci][1] = p0.y; z[ci][2] = p0.z; z[ci][3] = p0.w;
+      z[ci][4] = p1.x; z[ci][5] = p1.y; z[ci][6] = p1.z; z[ci][7] = p1.w;
+      ga[ci][0] = g0.x; ga[ci][1] = g0.y; ga[ci][2] = g0.z; ga[ci][3] = g0.w;
+      ga[ci][4] = g1.x; ga[ci][5] = g1.y; ga[ci][6] = g1.z; ga[ci][7] = g1.w;
+      be[ci][0] = b0.x; be[ci][1] = b0.y; be[ci][2] = b0.z; be[ci][3] = b0.w;
+      be[ci][4] = b1.x; be[ci][5] = b1.y; be[ci][6] = b1.z; be[ci][7] = b1.w;
+    }
+  }
 
   int tok;
   if (j.stage == 0) {
@@ -42,91 +64,98 @@ __global__ __launch_bounds__(256) void stage_kernel(StageJob j) {
   }
   tok = min(max(tok, 0), j.V - 1);  // a wild token from the caller must not leave the table
 
-  // gather + mix, 8 elements per thread per pass
-  const float* pz = j.pz + (int64_t)parent * D;
+  // gather + mix
   float lsum = 0.f;
-  for (int c = tid; c < D / 8; c += 256) {
-    const float4 p0 = *reinterpret_cast<const float4*>(pz + c * 8);
-    const float4 p1 = *reinterpret_cast<const float4*>(pz + c * 8 + 4);
-    float e[8];
-    if (BF16) {
-      const uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(j.emb) + (int64_t)tok * D + c * 8);
-      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        e[2 * q] = bf16_bits_to_f32(w[q] & 0xffffu);
-        e[2 * q + 1] = bf16_bits_to_f32(w[q] >> 16);
+  for (int ci = 0; ci < NCH; ++ci) {
+    const int c = tid + ci * 256;
+    if (c < nchunk) {
+      float e[8];
+      if (BF16) {
+        const uint4 raw =
+            *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(j.emb) + (int64_t)tok * D + c * 8);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          e[2 * q] = bf16_bits_to_f32(w[q] & 0xffffu);
+          e[2 * q + 1] = bf16_bits_to_f32(w[q] >> 16);
+        }
+      } else {
+        const float* er = static_cast<const float*>(j.emb) + (int64_t)tok * D + c * 8;
+        const float4 e0 = *reinterpret_cast<const float4*>(er);
+        const float4 e1 = *reinterpret_cast<const float4*>(er + 4);
+        e[0] = e0.x; e[1] = e0.y; e[2] = e0.z; e[3] = e0.w;
+        e[4] = e1.x; e[5] = e1.y; e[6] = e1.z; e[7] = e1.w;
       }
-    } else {
-      const float* er = static_cast<const float*>(j.emb) + (int64_t)tok * D + c * 8;
-      const float4 e0 = *reinterpret_cast<const float4*>(er);
-      const float4 e1 = *reinterpret_cast<const float4*>(er + 4);
-      e[0] = e0.x; e[1] = e0.y; e[2] = e0.z; e[3] = e0.w;
-      e[4] = e1.x; e[5] = e1.y; e[6] = e1.z; e[7] = e1.w;
-    }
-    const float p[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const float zz = j.w_s * p[q] + j.w_e * e[q];
-      z[c * 8 + q] = zz;
-      lsum += zz;
+      for (int q = 0; q < 8; ++q) {
+        z[ci][q] = j.w_s * z[ci][q] + j.w_e * e[q];
+        lsum += z[ci][q];
+      }
     }
   }
   const float mean = block_sum<256>(lsum, scratch) / (float)D;
   float lvar = 0.f;
-  for (int c = tid; c < D / 8; c += 256) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const float d = z[c * 8 + q] - mean;
-      lvar += d * d;
+  for (int ci = 0; ci < NCH; ++ci) {
+    if (tid + ci * 256 < nchunk) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const float d = z[ci][q] - mean;
+        lvar += d * d;
+      }
     }
   }
   const float var = block_sum<256>(lvar, scratch) / (float)D;
   const float rstd = 1.0f / sqrtf(var + j.eps);
 
-  for (int c = tid; c < D / 8; c += 256) {
-    const float4 g0 = *reinterpret_cast<const float4*>(j.gamma + c * 8);
-    const float4 g1 = *reinterpret_cast<const float4*>(j.gamma + c * 8 + 4);
-    const float4 b0 = *reinterpret_cast<const float4*>(j.beta + c * 8);
-    const float4 b1 = *reinterpret_cast<const float4*>(j.beta + c * 8 + 4);
-    const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
-    const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-    float s[8];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const float y = (z[c * 8 + q] - mean) * rstd * g[q] + b[q];
-      s[q] = 0.5f * y * (1.0f + erff(y * 0.70710678118654752440f));
-    }
-    if (BF16) {
-      uint4 o;
-      o.x = f32_to_bf16_bits(s[0]) | (f32_to_bf16_bits(s[1]) << 16);
-      o.y = f32_to_bf16_bits(s[2]) | (f32_to_bf16_bits(s[3]) << 16);
-      o.z = f32_to_bf16_bits(s[4]) | (f32_to_bf16_bits(s[5]) << 16);
-      o.w = f32_to_bf16_bits(s[6]) | (f32_to_bf16_bits(s[7]) << 16);
-      // tiled layout: row tile r/16, column fragment c/4, lane slot (c%4)*16 + r%16
-      const int64_t slot = ((int64_t)(r >> 4) * (D / 32) + (c >> 2)) * 64 + ((c & 3) << 4) + (r & 15);
-      reinterpret_cast<uint4*>(j.state_out)[slot] = o;
-      if (j.state_dbg) reinterpret_cast<uint4*>(j.state_dbg)[((int64_t)r * D) / 8 + c] = o;
-    } else {
-      float* so = static_cast<float*>(j.state_out) + (int64_t)r * D + c * 8;
-      *reinterpret_cast<float4*>(so) = make_float4(s[0], s[1], s[2], s[3]);
-      *reinterpret_cast<float4*>(so + 4) = make_float4(s[4], s[5], s[6], s[7]);
-      if (j.state_dbg) {
-        float* sd = static_cast<float*>(j.state_dbg) + (int64_t)r * D + c * 8;
-        *reinterpret_cast<float4*>(sd) = make_float4(s[0], s[1], s[2], s[3]);
-        *reinterpret_cast<float4*>(sd + 4) = make_float4(s[4], s[5], s[6], s[7]);
+  for (int ci = 0; ci < NCH; ++ci) {
+    const int c = tid + ci * 256;
+    if (c < nchunk) {
+      float s[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const float y = (z[ci][q] - mean) * rstd * ga[ci][q] + be[ci][q];
+        s[q] = 0.5f * y * (1.0f + erff(y * 0.70710678118654752440f));
+      }
+      if (BF16) {
+        uint4 o;
+        o.x = f32_to_bf16_bits(s[0]) | (f32_to_bf16_bits(s[1]) << 16);
+        o.y = f32_to_bf16_bits(s[2]) | (f32_to_bf16_bits(s[3]) << 16);
+        o.z = f32_to_bf16_bits(s[4]) | (f32_to_bf16_bits(s[5]) << 16);
+        o.w = f32_to_bf16_bits(s[6]) | (f32_to_bf16_bits(s[7]) << 16);
+        // tiled layout: row tile r/16, column fragment c/4, lane slot (c%4)*16 + r%16
+        const int64_t slot = ((int64_t)(r >> 4) * (D / 32) + (c >> 2)) * 64 + ((c & 3) << 4) + (r & 15);
+        reinterpret_cast<uint4*>(j.state_out)[slot] = o;
+        if (j.state_dbg) reinterpret_cast<uint4*>(j.state_dbg)[((int64_t)r * D) / 8 + c] = o;
+      } else {
+        float* so = static_cast<float*>(j.state_out) + (int64_t)r * D + c * 8;
+        *reinterpret_cast<float4*>(so) = make_float4(s[0], s[1], s[2], s[3]);
+        *reinterpret_cast<float4*>(so + 4) = make_float4(s[4], s[5], s[6], s[7]);
+        if (j.state_dbg) {
+          float* sd = static_cast<float*>(j.state_dbg) + (int64_t)r * D + c * 8;
+          *reinterpret_cast<float4*>(sd) = make_float4(s[0], s[1], s[2], s[3]);
+          *reinterpret_cast<float4*>(sd + 4) = make_float4(s[4], s[5], s[6], s[7]);
+        }
       }
     }
   }
 }
 
-hipError_t launch_stage(const StageJob& job, hipStream_t st) {
-  const size_t smem = (size_t)(job.D + 8) * sizeof(float);
-  if (job.bf16)
-    hipLaunchKernelGGL(stage_kernel<true>, dim3(job.R), dim3(256), smem, st, job);
-  else
-    hipLaunchKernelGGL(stage_kernel<false>, dim3(job.R), dim3(256), smem, st, job);
+template <bool BF16>
+static hipError_t launch_stage_t(const StageJob& job, hipStream_t st) {
+  const int nchunk = job.D / 8;
+  if (nchunk <= 256) hipLaunchKernelGGL((stage_kernel<BF16, 1>), dim3(job.R), dim3(256), 0, st, job);
+  else if (nchunk <= 512) hipLaunchKernelGGL((stage_kernel<BF16, 2>), dim3(job.R), dim3(256), 0, st, job);
+  else if (nchunk <= 1024) hipLaunchKernelGGL((stage_kernel<BF16, 4>), dim3(job.R), dim3(256), 0, st, job);
+  else if (nchunk <= 2048) hipLaunchKernelGGL((stage_kernel<BF16, 8>), dim3(job.R), dim3(256), 0, st, job);
+  else return hipErrorInvalidValue;
   return hipGetLastError();
+}
+
+hipError_t launch_stage(const StageJob& job, hipStream_t st) {
+  return job.bf16 ? launch_stage_t<true>(job, st) : launch_stage_t<false>(job, st);
 }
 
 // ---------------------------------------------------------------------------
@@ -134,7 +163,7 @@ hipError_t launch_stage(const StageJob& job, hipStream_t st) {
 // every leaf by the sum of its tokens' log-probabilities (added in stage order),
 // keep the B best.  One workgroup per sequence.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void tree_kernel(TreeJob j) {
+__global__ __launch_bounds__(1024) void tree_kernel(TreeJob j) {
   __shared__ float sc[kMaxLeaves];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int q = blockIdx.x;
@@ -142,7 +171,7 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeJob j) {
   const int k_last = j.top_k[n - 1];
   const int rows_last = L / k_last;
 
-  for (int rl = wave; rl < rows_last; rl += 4) {
+  for (int rl = wave; rl < rows_last; rl += 16) {
     const int64_t row = (int64_t)q * rows_last + rl;
     float v[kMaxTopK];
     int32_t ix[kMaxTopK];
@@ -159,7 +188,7 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeJob j) {
   __threadfence_block();
   __syncthreads();
 
-  for (int leaf = tid; leaf < L; leaf += 256) {
+  for (int leaf = tid; leaf < L; leaf += 1024) {
     float score = 0.f;
     int64_t row = q;
     int stride = L;
@@ -174,7 +203,7 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeJob j) {
   }
   __syncthreads();
 
-  for (int leaf = tid; leaf < L; leaf += 256) {
+  for (int leaf = tid; leaf < L; leaf += 1024) {
     const float s = sc[leaf];
     int pos = 0;
     for (int o = 0; o < L; ++o) {
@@ -199,7 +228,7 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeJob j) {
 }
 
 hipError_t launch_tree(const TreeJob& job, hipStream_t st) {
-  hipLaunchKernelGGL(tree_kernel, dim3(job.batch), dim3(256), 0, st, job);
+  hipLaunchKernelGGL(tree_kernel, dim3(job.batch), dim3(1024), 0, st, job);
   return hipGetLastError();
 }
 

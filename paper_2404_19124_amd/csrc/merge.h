@@ -6,11 +6,35 @@
 
 namespace specdraft {
 
+// Insert (v, i) into a list kept sorted by "larger value, then smaller index";
+// the last entry falls off.
+template <int K>
+__device__ __forceinline__ void list_insert(float (&tv)[K], int32_t (&ti)[K], float v, int32_t i) {
+  float cv = v;
+  int32_t ci = i;
+#pragma unroll
+  for (int q = 0; q < K; ++q) {
+    const bool gt = before(cv, ci, tv[q], ti[q]);
+    const float ov = tv[q];
+    const int32_t oi = ti[q];
+    tv[q] = gt ? cv : ov;
+    ti[q] = gt ? ci : oi;
+    cv = gt ? ov : cv;
+    ci = gt ? oi : ci;
+  }
+}
+
 // All 64 lanes of a wave call this for the same row; every lane receives the
 // result.  out_val / out_idx must be indexed with compile-time constants by the
 // caller (they live in registers).  Candidates of different parts never share a
 // vocabulary index, so (value, index) is a strict total order.
-__device__ __forceinline__ void wave_merge_partials(const Partials& p, int64_t row, int nparts, int k,
+//
+// Latency matters here (this sits on the serial chain between two heads at
+// batch 1): every lane first issues the loads of four parts at once, then folds
+// them into a sorted register list; the k results are popped with wave-wide
+// reductions, no memory traffic in between.
+template <int K>
+__device__ __forceinline__ void wave_merge_partials_k(const Partials& p, int64_t row, int nparts, int k,
                                                     float (&out_val)[kMaxTopK], int32_t (&out_idx)[kMaxTopK],
                                                     float& lse) {
   const int lane = threadIdx.x & 63;
@@ -19,38 +43,83 @@ __device__ __forceinline__ void wave_merge_partials(const Partials& p, int64_t r
   const float* pv = p.val + row * (int64_t)nparts * k;
   const int32_t* pi = p.idx + row * (int64_t)nparts * k;
 
-  float mx = SPEC_NEG_INF;
-  for (int c = lane; c < nparts; c += 64) mx = fmaxf(mx, pm[c]);
-  mx = wave_max(mx);
-  float sum = 0.f;
-  for (int c = lane; c < nparts; c += 64) {
-    const float m = pm[c];
-    if (m > SPEC_NEG_INF) sum += ps[c] * expf(m - mx);
+  float tv[K];
+  int32_t ti[K];
+#pragma unroll
+  for (int q = 0; q < K; ++q) { tv[q] = SPEC_NEG_INF; ti[q] = kIdxNone; }
+  float run_m = SPEC_NEG_INF, run_s = 0.f;
+
+  constexpr int UN = 4;
+  for (int p0 = 0; p0 < nparts; p0 += 64 * UN) {
+    float lm[UN], ls[UN], lv[UN][K];
+    int32_t li[UN][K];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int part = p0 + u * 64 + lane;
+      const bool ok = part < nparts;
+      lm[u] = ok ? pm[part] : SPEC_NEG_INF;
+      ls[u] = ok ? ps[part] : 0.f;
+#pragma unroll
+      for (int j = 0; j < K; ++j) {
+        const bool okj = ok && j < k;
+        lv[u][j] = okj ? pv[(int64_t)part * k + j] : SPEC_NEG_INF;
+        li[u][j] = okj ? pi[(int64_t)part * k + j] : kIdxNone;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      if (lm[u] > SPEC_NEG_INF) {
+        const float mn = fmaxf(run_m, lm[u]);
+        run_s = run_s * expf(run_m - mn) + ls[u] * expf(lm[u] - mn);
+        run_m = mn;
+      }
+#pragma unroll
+      for (int j = 0; j < K; ++j)
+        if (j < k && before(lv[u][j], li[u][j], tv[K - 1], ti[K - 1]))
+          list_insert<K>(tv, ti, lv[u][j], li[u][j]);
+    }
   }
-  sum = wave_sum(sum);
+
+  const float mx = wave_max(run_m);
+  const float sum = wave_sum(run_m > SPEC_NEG_INF ? run_s * expf(run_m - mx) : 0.f);
   lse = mx + logf(sum);
 
-  const int total = nparts * k;
-  float lastv = __builtin_huge_valf();
-  int32_t lasti = -1;
 #pragma unroll
   for (int j = 0; j < kMaxTopK; ++j) {
     out_val[j] = SPEC_NEG_INF;
     out_idx[j] = kIdxNone;
+  }
+#pragma unroll
+  for (int j = 0; j < K; ++j) {
     if (j < k) {
-      float bv = SPEC_NEG_INF;
-      int32_t bi = kIdxNone;
-      for (int c = lane; c < total; c += 64) {
-        const float v = pv[c];
-        const int32_t i = pi[c];
-        if (before(lastv, lasti, v, i) && before(v, i, bv, bi)) { bv = v; bi = i; }
-      }
+      float bv = tv[0];
+      int32_t bi = ti[0];
       wave_best(bv, bi);
+      if (ti[0] == bi && tv[0] == bv) {  // the owner of the winner pops it
+#pragma unroll
+        for (int q = 0; q + 1 < K; ++q) { tv[q] = tv[q + 1]; ti[q] = ti[q + 1]; }
+        tv[K - 1] = SPEC_NEG_INF;
+        ti[K - 1] = kIdxNone;
+      }
       out_val[j] = bv;
       out_idx[j] = bi;
-      lastv = bv;
-      lasti = bi;
     }
+  }
+}
+
+// k is uniform over the launch: pick the list size that just holds it, so that
+// the common narrow heads (k = 1..3) do not pay for eight slots.
+__device__ __forceinline__ void wave_merge_partials(const Partials& p, int64_t row, int nparts, int k,
+                                                    float (&out_val)[kMaxTopK], int32_t (&out_idx)[kMaxTopK],
+                                                    float& lse) {
+  switch (k) {
+    case 1: wave_merge_partials_k<1>(p, row, nparts, k, out_val, out_idx, lse); break;
+    case 2: wave_merge_partials_k<2>(p, row, nparts, k, out_val, out_idx, lse); break;
+    case 3: wave_merge_partials_k<3>(p, row, nparts, k, out_val, out_idx, lse); break;
+    case 4: wave_merge_partials_k<4>(p, row, nparts, k, out_val, out_idx, lse); break;
+    case 5:
+    case 6: wave_merge_partials_k<6>(p, row, nparts, k, out_val, out_idx, lse); break;
+    default: wave_merge_partials_k<8>(p, row, nparts, k, out_val, out_idx, lse); break;
   }
 }
 

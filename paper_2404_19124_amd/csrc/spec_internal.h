@@ -66,7 +66,9 @@ struct HeadJob {
 // weights streamed tile by tile straight into registers.  nparts = grid size.
 bool skinny_fits(int R, int kt);
 int skinny_grid(int n_cu);
-hipError_t launch_head_skinny(const HeadJob& job, int n_cu, hipStream_t st);
+// ev_start / ev_stop (may be null) receive the kernel's own begin / end timestamps.
+hipError_t launch_head_skinny(const HeadJob& job, int n_cu, hipStream_t st, hipEvent_t ev_start = nullptr,
+                              hipEvent_t ev_stop = nullptr);
 
 // Any number of rows: workgroup tiles of (16*MI rows) x (64*NI weight rows).
 // One matrix per launch (head with top-k partials or store; or projection store).
@@ -75,7 +77,8 @@ struct GemmPlan {
   int m_tiles, n_tiles;
 };
 GemmPlan plan_gemm(int R, int n_rows_weight);
-hipError_t launch_head_gemm(const HeadJob& job, bool proj_matrix, const GemmPlan& plan, hipStream_t st);
+hipError_t launch_head_gemm(const HeadJob& job, bool proj_matrix, const GemmPlan& plan, hipStream_t st,
+                            hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
 // ---- contraction, float32 (correctness configuration) ---------------------
 // out[r * ldo + v] = sum_k a[r * lda + k] * w[v * ldw + k]

@@ -100,6 +100,7 @@ static spec_status_t check_config(const spec_config_t* c) {
     return fail(SPEC_EINVAL, "n_predict = %d outside [1, %d]", c->n_predict, SPEC_MAX_STAGES);
   if (c->emb_dim < 1 || c->inner_dim < 1 || c->vocab < 1)
     return fail(SPEC_EINVAL, "emb_dim, inner_dim and vocab must be positive");
+  if (c->inner_dim > 16384) return fail(SPEC_ESHAPE, "inner_dim = %d exceeds 16384", c->inner_dim);
   if (c->weight_dtype != SPEC_F32 && c->weight_dtype != SPEC_BF16)
     return fail(SPEC_EDTYPE, "weight_dtype = %d is neither SPEC_F32 nor SPEC_BF16", c->weight_dtype);
   if (c->weight_dtype == SPEC_BF16 && (c->emb_dim % 64 || c->inner_dim % 64))
@@ -259,16 +260,16 @@ extern "C" spec_status_t spec_model_scalars(const spec_model_t* m, float* state_
   return SPEC_OK;
 }
 
-static int prof_begin(spec_model* m, int kernel, int rows, int weight_rows, int k, hipStream_t st) {
+// Reserves a record slot; the launch attaches the slot's two events to the kernel
+// dispatch itself, so they carry the kernel's own begin / end timestamps.
+static int prof_slot(spec_model* m, int kernel, int rows, int weight_rows, int k) {
   if (m->prof_cap <= 0 || m->prof_n >= m->prof_cap) return -1;
   const int slot = m->prof_n++;
   m->rec[slot] = {kernel, rows, weight_rows, k};
-  (void)hipEventRecord(m->ev[2 * slot], st);
   return slot;
 }
-static void prof_end(spec_model* m, int slot, hipStream_t st) {
-  if (slot >= 0) (void)hipEventRecord(m->ev[2 * slot + 1], st);
-}
+#define EV0(slot) ((slot) >= 0 ? m->ev[2 * (slot)] : nullptr)
+#define EV1(slot) ((slot) >= 0 ? m->ev[2 * (slot) + 1] : nullptr)
 
 extern "C" spec_status_t spec_profile_enable(spec_model_t* m, int32_t capacity) {
   if (!m) return fail(SPEC_EINVAL, "model is NULL");
@@ -341,9 +342,8 @@ static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, c
   if (skinny_fits(R, job.kt)) {
     job.nparts = skinny_grid(m->n_cu);
     *nparts = job.nparts;
-    const int slot = prof_begin(m, 0, R, job.n_head + job.n_proj, K, st);
-    HIP_TRY(launch_head_skinny(job, m->n_cu, st));
-    prof_end(m, slot, st);
+    const int slot = prof_slot(m, 0, R, job.n_head + job.n_proj, K);
+    HIP_TRY(launch_head_skinny(job, m->n_cu, st, EV0(slot), EV1(slot)));
     return SPEC_OK;
   }
   // general path wants tiled states
@@ -359,15 +359,13 @@ static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, c
     *nparts = pl.n_tiles;
     if (!out_head && (int64_t)R * pl.n_tiles > m->part_rows_parts)
       return fail(SPEC_ESHAPE, "internal: partial workspace too small (%d rows x %d parts)", R, pl.n_tiles);
-    const int slot = prof_begin(m, pl.mi == 2 ? 1 : (pl.mi == 4 ? 2 : 3), R, job.n_head, K, st);
-    HIP_TRY(launch_head_gemm(job, false, pl, st));
-    prof_end(m, slot, st);
+    const int slot = prof_slot(m, pl.mi == 2 ? 1 : (pl.mi == 4 ? 2 : 3), R, job.n_head, K);
+    HIP_TRY(launch_head_gemm(job, false, pl, st, EV0(slot), EV1(slot)));
   }
   if (proj_stage >= 0) {
     GemmPlan pl = plan_gemm(R, D);
-    const int slot = prof_begin(m, pl.mi == 2 ? 1 : (pl.mi == 4 ? 2 : 3), R, job.n_proj, K, st);
-    HIP_TRY(launch_head_gemm(job, true, pl, st));
-    prof_end(m, slot, st);
+    const int slot = prof_slot(m, pl.mi == 2 ? 1 : (pl.mi == 4 ? 2 : 3), R, job.n_proj, K);
+    HIP_TRY(launch_head_gemm(job, true, pl, st, EV0(slot), EV1(slot)));
   }
   return SPEC_OK;
 }
