@@ -41,6 +41,7 @@ def main() -> int:
     ap.add_argument("--workload", default="llama7b_b1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--verbose", action="store_true", help="per-shape timing of the contraction launches on stderr")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding in "
@@ -104,6 +105,17 @@ def main() -> int:
         # algorithmic traffic of a launch: the weights once, the state rows once
         d["bytes"] += 2.0 * r["weight_rows"] * r["k"] + 2.0 * r["rows"] * r["k"]
         d["flops"] += 2.0 * r["rows"] * r["weight_rows"] * r["k"]
+    if args.verbose:
+        groups = {}
+        for r in recs:
+            g = groups.setdefault((r["kernel"], r["rows"], r["weight_rows"], r["k"]), [0.0, 0])
+            g[0] += r["ms"]
+            g[1] += 1
+        for (kern, rows, wrows, kk), (ms, cnt) in sorted(groups.items()):
+            us = ms / cnt * 1e3
+            print("  %-24s rows %5d x weights %6d x k %5d : %8.2f us  %7.1f GB/s  %7.1f TFLOP/s  (%d launches)"
+                  % (KERNEL_NAMES[kern], rows, wrows, kk, us, (2.0 * wrows * kk + 2.0 * rows * kk) / us / 1e3,
+                     2.0 * rows * wrows * kk / us / 1e6, cnt), file=sys.stderr)
     dom = max(by_kernel, key=lambda k: by_kernel[k]["ms"])
     d = by_kernel[dom]
     avg_ms = d["ms"] / d["n"]

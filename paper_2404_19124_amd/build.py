@@ -42,9 +42,15 @@ def hipcc() -> str:
     return exe
 
 
+# Per-file additions.  The dense contraction keeps its accumulators in VGPRs: with the
+# default heuristic the register allocator shuffles 128 accumulators between AGPRs and
+# VGPRs on every loop trip.
+EXTRA = {"kernels_head_gemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [hipcc(), *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)

@@ -20,12 +20,16 @@
 //    varying fastest: workgroups that share weights run together on one L2.
 #include <hip/hip_ext.h>
 
+#include <cstring>
+
 #include "device_utils.h"
 #include "spec_internal.h"
 
 namespace specdraft {
 
-constexpr int KS = 2;  // K-steps (of 32) per slab
+constexpr int KS = 2;   // K-steps (of 32) per slab
+constexpr int PD = 3;   // slabs of global loads in flight ahead of the matrix cores
+constexpr int NSET = PD + 1;
 
 GemmPlan plan_gemm(int R, int n_rows_weight) {
   GemmPlan pl;
@@ -37,53 +41,63 @@ GemmPlan plan_gemm(int R, int n_rows_weight) {
   return pl;
 }
 
+// Up to two weight matrices share one launch (head, then the next stage's
+// projection): their workgroup tiles form one list, so the small projection
+// fills the tail of the head's last wave of workgroups instead of a launch of its own.
 struct GemmArgs {
-  const uint4* w;     // packed weights
-  int nt_total;       // 16-row tiles of the weight matrix
-  int n_valid;        // valid weight rows
+  const u32x4* w[2];  // packed weights
+  int nt_total[2];    // 16-row tiles of each weight matrix
+  int n_valid[2];     // valid weight rows
+  int n_tiles[2];     // workgroup tiles along the weight rows
+  float* out[2];      // store epilogue target (matrix 0: only if mode0 == 1)
+  int64_t ldo[2];
+  int mode0;          // matrix 0: 0 = top-k partials, 1 = store.  Matrix 1 always stores.
   int kt;
-  const uint4* b;     // packed states
+  const u32x4* b;     // packed states
   int R, mt_total;
-  int m_tiles, n_tiles, chunk;  // chunk = workgroup tiles per XCD
-  int mode;           // 0: top-k partials, 1: store
+  int m_tiles, chunk; // chunk = workgroup tiles per XCD
   int k_top;
   Partials part;
   int nparts;
-  float* out;
-  int64_t ldo;
 };
 
 template <int MI, int NI>
 __global__ __launch_bounds__(256) void head_gemm_kernel(GemmArgs p) {
   extern __shared__ __align__(16) unsigned char smem[];
-  uint4* ldsB = reinterpret_cast<uint4*>(smem);  // [2][MI*KS*64]
+  u32x4* ldsB = reinterpret_cast<u32x4*>(smem);  // [2][MI*KS*64]
   constexpr int SLAB = MI * KS * 64;             // slots per slab
-  constexpr int SPT = (SLAB + 255) / 256;        // staging slots per thread
+  constexpr int SPT = SLAB / 256;                // staging slots per thread
+  static_assert(SLAB % 256 == 0, "a slab is staged by whole passes of the workgroup");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
   // XCD-aware tile id: hardware places workgroup ids round-robin over 8 XCDs
   const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
   if (seq >= p.chunk) return;
   const int tile_id = xcd * p.chunk + seq;
-  if (tile_id >= p.m_tiles * p.n_tiles) return;
-  const int ntile = tile_id / p.m_tiles, mtile = tile_id - ntile * p.m_tiles;
+  if (tile_id >= p.m_tiles * (p.n_tiles[0] + p.n_tiles[1])) return;
+  int ntile = tile_id / p.m_tiles;
+  const int mtile = tile_id - ntile * p.m_tiles;
+  const int mat = ntile >= p.n_tiles[0] ? 1 : 0;
+  ntile -= mat ? p.n_tiles[0] : 0;
+  const int mode = mat ? 1 : p.mode0;
+  const int n_valid = p.n_valid[mat];
 
   const int kt = p.kt;
   // weight fragments of this wave
-  const uint4* wptr[NI];
+  const u32x4* wptr[NI];
   int nt[NI];
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni) {
     nt[ni] = (ntile * 4 + wave) * NI + ni;
-    const int ntc = min(nt[ni], p.nt_total - 1);
-    wptr[ni] = p.w + (int64_t)ntc * kt * 64 + lane;
+    const int ntc = min(nt[ni], p.nt_total[mat] - 1);
+    wptr[ni] = p.w[mat] + (int64_t)ntc * kt * 64 + lane;
   }
   // staging sources of this thread
-  const uint4* sptr[SPT];
+  const u32x4* sptr[SPT];
 #pragma unroll
   for (int s = 0; s < SPT; ++s) {
     const int i = s * 256 + tid;
-    const int mtl = min(i / (KS * 64), MI - 1), rem = i % (KS * 64);
+    const int mtl = i / (KS * 64), rem = i % (KS * 64);
     const int mt = min(mtile * MI + mtl, p.mt_total - 1);
     sptr[s] = p.b + (int64_t)mt * kt * 64 + rem;
   }
@@ -94,61 +108,62 @@ __global__ __launch_bounds__(256) void head_gemm_kernel(GemmArgs p) {
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
+  // Software pipeline over K-slabs.  Global loads (weight fragments into register
+  // set a[], state slots into register set g[]) run PD slabs ahead; a state slab
+  // is moved from its registers to LDS one slab before it is needed (LDS double
+  // buffer, one barrier per slab).  NSET = PD + 1 register sets rotate through a
+  // loop unrolled NSET times, so every index below is a compile-time constant.
   const int nslab = kt / KS;
-  uint4 a_cur[NI][KS], a_nxt[NI][KS], stg[SPT];
-  // prologue: slab 0
+  u32x4 a[NSET][NI][KS], g[NSET][SPT];
+  auto load_slab = [&](u32x4 (&aw)[NI][KS], u32x4 (&gs)[SPT], int sl) {
+    const int64_t off = (int64_t)sl * KS * 64;
 #pragma unroll
-  for (int s = 0; s < SPT; ++s)
-    if (s * 256 + tid < SLAB) stg[s] = sptr[s][0];
+    for (int s = 0; s < SPT; ++s) gs[s] = sptr[s][off];
 #pragma unroll
-  for (int ni = 0; ni < NI; ++ni)
+    for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-    for (int ts = 0; ts < KS; ++ts) a_cur[ni][ts] = wptr[ni][ts * 64];
+      for (int ts = 0; ts < KS; ++ts) aw[ni][ts] = wptr[ni][off + ts * 64];
+  };
+  auto store_s = [&](const u32x4 (&gs)[SPT], int buf) {
 #pragma unroll
-  for (int s = 0; s < SPT; ++s)
-    if (s * 256 + tid < SLAB) ldsB[s * 256 + tid] = stg[s];
-  __syncthreads();
-
-  for (int sl = 0; sl < nslab; ++sl) {
-    const int cur = sl & 1;
-    const bool more = sl + 1 < nslab;
-    if (more) {
-      const int64_t off = (int64_t)(sl + 1) * KS * 64;
-#pragma unroll
-      for (int s = 0; s < SPT; ++s)
-        if (s * 256 + tid < SLAB) stg[s] = sptr[s][off];
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-        for (int ts = 0; ts < KS; ++ts) a_nxt[ni][ts] = wptr[ni][off + ts * 64];
-    }
+    for (int s = 0; s < SPT; ++s) ldsB[buf * SLAB + s * 256 + tid] = gs[s];
+  };
+  auto compute = [&](const u32x4 (&aw)[NI][KS], int buf) {
 #pragma unroll
     for (int ts = 0; ts < KS; ++ts) {
-      uint4 bf[MI];
+      u32x4 bf[MI];
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi) bf[mi] = ldsB[cur * SLAB + (mi * KS + ts) * 64 + lane];
+      for (int mi = 0; mi < MI; ++mi) bf[mi] = ldsB[buf * SLAB + (mi * KS + ts) * 64 + lane];
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_cur[ni][ts]),
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, aw[ni][ts]),
                                                                 __builtin_bit_cast(bf16x8, bf[mi]), acc[mi][ni], 0, 0, 0);
     }
-    if (more) {
+  };
+
 #pragma unroll
-      for (int s = 0; s < SPT; ++s)
-        if (s * 256 + tid < SLAB) ldsB[(cur ^ 1) * SLAB + s * 256 + tid] = stg[s];
+  for (int q = 0; q < PD; ++q)
+    if (q < nslab) load_slab(a[q], g[q], q);
+  store_s(g[0], 0);
+  __syncthreads();
+  for (int base = 0; base < nslab; base += NSET) {
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-        for (int ts = 0; ts < KS; ++ts) a_cur[ni][ts] = a_nxt[ni][ts];
+    for (int u = 0; u < NSET; ++u) {
+      const int sl = base + u;
+      if (sl < nslab) {
+        if (sl + PD < nslab) load_slab(a[(u + PD) % NSET], g[(u + PD) % NSET], sl + PD);
+        compute(a[u], u & 1);
+        if (sl + 1 < nslab) store_s(g[(u + 1) % NSET], (u + 1) & 1);
+        __syncthreads();
+      }
     }
-    __syncthreads();
   }
 
   // ------------------------------------------------------------------ epilogue
   const int col = lane & 15, grp = lane >> 4;
-  if (p.mode == 1) {
+  if (mode == 1) {
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
       const int r = (mtile * MI + mi) * 16 + col;
@@ -156,13 +171,13 @@ __global__ __launch_bounds__(256) void head_gemm_kernel(GemmArgs p) {
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni) {
         const int v0 = nt[ni] * 16 + grp * 4;
-        float* o = p.out + (int64_t)r * p.ldo + v0;
-        if (v0 + 3 < p.n_valid && (p.ldo & 3) == 0) {
+        float* o = p.out[mat] + (int64_t)r * p.ldo[mat] + v0;
+        if (v0 + 3 < n_valid && (p.ldo[mat] & 3) == 0) {
           *reinterpret_cast<float4*>(o) = make_float4(acc[mi][ni][0], acc[mi][ni][1], acc[mi][ni][2], acc[mi][ni][3]);
         } else {
 #pragma unroll
           for (int i = 0; i < 4; ++i)
-            if (v0 + i < p.n_valid) o[i] = acc[mi][ni][i];
+            if (v0 + i < n_valid) o[i] = acc[mi][ni][i];
         }
       }
     }
@@ -188,7 +203,7 @@ __global__ __launch_bounds__(256) void head_gemm_kernel(GemmArgs p) {
       for (int i = 0; i < 4; ++i) {
         const int v = nt[ni] * 16 + grp * 4 + i;
         vx[ni * 4 + i] = v;
-        x[ni * 4 + i] = v < p.n_valid ? acc[mi][ni][i] : SPEC_NEG_INF;
+        x[ni * 4 + i] = v < n_valid ? acc[mi][ni][i] : SPEC_NEG_INF;
       }
     float lastv = __builtin_huge_valf();
     int32_t lasti = -1;
@@ -272,33 +287,39 @@ static size_t gemm_smem(int mi) {
   return slabs > epi ? slabs : epi;
 }
 
-hipError_t launch_head_gemm(const HeadJob& job, bool proj_matrix, const GemmPlan& pl, hipStream_t st,
-                            hipEvent_t ev_start, hipEvent_t ev_stop) {
+hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t st, hipEvent_t ev_start,
+                            hipEvent_t ev_stop) {
   GemmArgs a;
-  a.w = static_cast<const uint4*>(proj_matrix ? job.w_proj : job.w_head);
-  a.nt_total = proj_matrix ? job.vt_proj : job.vt_head;
-  a.n_valid = proj_matrix ? job.n_proj : job.n_head;
+  memset(&a, 0, sizeof(a));
+  int nm = 0;
+  if (job.vt_head > 0) {
+    a.w[nm] = static_cast<const u32x4*>(job.w_head);
+    a.nt_total[nm] = job.vt_head;
+    a.n_valid[nm] = job.n_head;
+    a.n_tiles[nm] = (job.n_head + 64 * pl.ni - 1) / (64 * pl.ni);
+    a.out[nm] = job.out_head;
+    a.ldo[nm] = job.ld_head;
+    a.mode0 = job.out_head ? 1 : 0;
+    ++nm;
+  }
+  if (job.vt_proj > 0) {
+    a.w[nm] = static_cast<const u32x4*>(job.w_proj);
+    a.nt_total[nm] = job.vt_proj;
+    a.n_valid[nm] = job.n_proj;
+    a.n_tiles[nm] = (job.n_proj + 64 * pl.ni - 1) / (64 * pl.ni);
+    a.out[nm] = job.out_proj;
+    a.ldo[nm] = job.ld_proj;
+    if (nm == 0) a.mode0 = 1;
+    ++nm;
+  }
+  if (nm == 0) return hipErrorInvalidValue;
   a.kt = job.kt;
-  a.b = static_cast<const uint4*>(job.b_src);
+  a.b = static_cast<const u32x4*>(job.b_src);
   a.R = job.R;
   a.mt_total = (job.R + 15) / 16;
   a.m_tiles = pl.m_tiles;
-  a.n_tiles = pl.n_tiles;
-  const int total = pl.m_tiles * pl.n_tiles;
+  const int total = pl.m_tiles * (a.n_tiles[0] + a.n_tiles[1]);
   a.chunk = (total + 7) / 8;
-  if (proj_matrix) {
-    a.mode = 1;
-    a.out = job.out_proj;
-    a.ldo = job.ld_proj;
-  } else if (job.out_head) {
-    a.mode = 1;
-    a.out = job.out_head;
-    a.ldo = job.ld_head;
-  } else {
-    a.mode = 0;
-    a.out = nullptr;
-    a.ldo = 0;
-  }
   a.k_top = job.k_top;
   a.part = job.part;
   a.nparts = job.nparts;

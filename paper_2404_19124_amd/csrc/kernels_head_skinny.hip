@@ -45,7 +45,7 @@ template <int NS, int DEPTH, bool EXACT>
 __global__ __launch_bounds__(kSkinnyWaves * 64) void head_skinny_kernel(HeadJob p) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int kt = p.kt, R = p.R;
-  uint4* ldsB = reinterpret_cast<uint4*>(smem);  // [kt][4][R] slots of 8 bf16
+  u32x4* ldsB = reinterpret_cast<u32x4*>(smem);  // [kt][4][R] slots of 8 bf16
   const size_t bytesB = ((size_t)kt * 4 * R * 16 + 255) & ~(size_t)255;
   f32x4* ldsP = reinterpret_cast<f32x4*>(smem + bytesB);  // [2][waves][64]
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -57,22 +57,22 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void head_skinny_kernel(HeadJob 
   const int s0 = min(w * spw, kt);
   const int ns = EXACT ? NS : min(kt, s0 + spw) - s0;
   const int g = lane >> 4, nn = min(lane & 15, R - 1);
-  const uint4* bptr = ldsB + ((int64_t)s0 * 4 + g) * R + nn;  // step t: + t*4*R
+  const u32x4* bptr = ldsB + ((int64_t)s0 * 4 + g) * R + nn;  // step t: + t*4*R
   const int total = p.vt_head + p.vt_proj;
-  const uint4* wh = static_cast<const uint4*>(p.w_head);
-  const uint4* wp = static_cast<const uint4*>(p.w_proj);
-  auto tile_ptr = [&](int tile) -> const uint4* {
-    const uint4* base = tile < p.vt_head ? wh + (int64_t)tile * kt * 64 : wp + (int64_t)(tile - p.vt_head) * kt * 64;
+  const u32x4* wh = static_cast<const u32x4*>(p.w_head);
+  const u32x4* wp = static_cast<const u32x4*>(p.w_proj);
+  auto tile_ptr = [&](int tile) -> const u32x4* {
+    const u32x4* base = tile < p.vt_head ? wh + (int64_t)tile * kt * 64 : wp + (int64_t)(tile - p.vt_head) * kt * 64;
     return base + (int64_t)s0 * 64 + lane;
   };
 
   const int G = gridDim.x;
-  uint4 a[DEPTH][NS];
+  u32x4 a[DEPTH][NS];
 #pragma unroll
   for (int d = 0; d < DEPTH; ++d) {
     const int tile = blockIdx.x + d * G;
     if (tile < total) {
-      const uint4* ptr = tile_ptr(tile);
+      const u32x4* ptr = tile_ptr(tile);
 #pragma unroll
       for (int t = 0; t < NS; ++t)
         if (EXACT || t < ns) a[d][t] = ptr[t * 64];
@@ -82,11 +82,11 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void head_skinny_kernel(HeadJob 
   // ---- states -> LDS, trimmed to R rows: slot (t, g, n) = row n, columns t*32 + g*8 .. +8
   for (int slot = tid; slot < kt * 4 * R; slot += NT) {
     const int n = slot % R, tg = slot / R;
-    uint4 v;
+    u32x4 v;
     if (p.b_rowmajor)
-      v = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(p.b_src) + (int64_t)n * p.b_ld + tg * 8);
+      v = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.b_src) + (int64_t)n * p.b_ld + tg * 8);
     else
-      v = static_cast<const uint4*>(p.b_src)[(int64_t)(tg >> 2) * 64 + (tg & 3) * 16 + n];
+      v = static_cast<const u32x4*>(p.b_src)[(int64_t)(tg >> 2) * 64 + (tg & 3) * 16 + n];
     ldsB[slot] = v;
   }
   __syncthreads();
@@ -107,12 +107,12 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void head_skinny_kernel(HeadJob 
       if (tile < total) {
         const int next = tile + DEPTH * G;
         const bool has_next = next < total;
-        const uint4* nptr = tile_ptr(has_next ? next : tile);
+        const u32x4* nptr = tile_ptr(has_next ? next : tile);
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int t = 0; t < NS; ++t) {
           if (EXACT || t < ns) {
-            const uint4 b = bptr[(int64_t)t * 4 * R];
+            const u32x4 b = bptr[(int64_t)t * 4 * R];
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[d][t]),
                                                           __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
             if (has_next) a[d][t] = nptr[t * 64];

@@ -12,6 +12,9 @@ constexpr int kMaxLeaves = 4096;  // = SPEC_MAX_LEAVES
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+// 16 raw bytes as a native vector (HIP's uint4 is a struct: copies of it can become
+// memcpy calls that keep small arrays out of registers)
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
 // ---------------------------------------------------------------------------
 // Tiled ("packed") bf16 layout.  A row-major matrix X[N][K] (K % 32 == 0) is
@@ -71,14 +74,14 @@ hipError_t launch_head_skinny(const HeadJob& job, int n_cu, hipStream_t st, hipE
                               hipEvent_t ev_stop = nullptr);
 
 // Any number of rows: workgroup tiles of (16*MI rows) x (64*NI weight rows).
-// One matrix per launch (head with top-k partials or store; or projection store).
+// Head (top-k partials or store) and, if present, the projection (store) in one launch.
 struct GemmPlan {
   int mi, ni;       // fragments per wave in M (state rows) and N (weight rows)
   int m_tiles, n_tiles;
 };
 GemmPlan plan_gemm(int R, int n_rows_weight);
-hipError_t launch_head_gemm(const HeadJob& job, bool proj_matrix, const GemmPlan& plan, hipStream_t st,
-                            hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& plan, hipStream_t st, hipEvent_t ev_start = nullptr,
+                            hipEvent_t ev_stop = nullptr);
 
 // ---- contraction, float32 (correctness configuration) ---------------------
 // out[r * ldo + v] = sum_k a[r * lda + k] * w[v * ldw + k]

@@ -353,20 +353,15 @@ static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, c
     job.b_rowmajor = 0;
   }
   *nparts = 1;
+  GemmPlan pl = plan_gemm(R, stage >= 0 ? V : D);
   if (stage >= 0) {
-    GemmPlan pl = plan_gemm(R, V);
     job.nparts = pl.n_tiles;
     *nparts = pl.n_tiles;
     if (!out_head && (int64_t)R * pl.n_tiles > m->part_rows_parts)
       return fail(SPEC_ESHAPE, "internal: partial workspace too small (%d rows x %d parts)", R, pl.n_tiles);
-    const int slot = prof_slot(m, pl.mi == 2 ? 1 : (pl.mi == 4 ? 2 : 3), R, job.n_head, K);
-    HIP_TRY(launch_head_gemm(job, false, pl, st, EV0(slot), EV1(slot)));
   }
-  if (proj_stage >= 0) {
-    GemmPlan pl = plan_gemm(R, D);
-    const int slot = prof_slot(m, pl.mi == 2 ? 1 : (pl.mi == 4 ? 2 : 3), R, job.n_proj, K);
-    HIP_TRY(launch_head_gemm(job, true, pl, st, EV0(slot), EV1(slot)));
-  }
+  const int slot = prof_slot(m, pl.mi == 2 ? 1 : (pl.mi == 4 ? 2 : 3), R, job.n_head + job.n_proj, K);
+  HIP_TRY(launch_head_gemm(job, pl, st, EV0(slot), EV1(slot)));
   return SPEC_OK;
 }
 
