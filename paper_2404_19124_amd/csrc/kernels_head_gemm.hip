@@ -3,21 +3,26 @@
 // per stage for 64 sequences with a 5/3/2 tree).
 //
 // Design for CDNA4:
-//  * workgroup = 4 waves; workgroup tile = (16*MI state rows) x (4 * NI * 16
-//    weight rows); every wave owns NI*16 weight rows and all 16*MI state rows,
-//    so no weight fragment is loaded twice inside a workgroup;
+//  * workgroup = 4 waves, one per SIMD; workgroup tile = (16*MI state rows) x
+//    (4 * NI * 16 weight rows); every wave owns NI*16 weight rows and all 16*MI
+//    state rows, so no weight fragment is loaded twice inside a workgroup;
 //  * weights come from the tiled layout as coalesced 1 KiB fragments straight
-//    into registers (A operand of v_mfma_f32_16x16x32_bf16), prefetched one
-//    K-slab ahead; states (B operand) are staged through LDS, double-buffered,
-//    one barrier per slab.  The states are already stored in fragment order, so
-//    the global->LDS copy is linear and the LDS reads are conflict-free;
-//  * accumulator lane l holds state row l%16 and 4 weight rows: the softmax /
-//    top-k reduction over the vocabulary is mostly lane-local.  The epilogue
-//    keeps, per (row, workgroup tile), max, sum-exp and the k best logits;
-//    logits are never written to memory (unless the store epilogue is asked for);
-//  * workgroup ids are remapped so that the tiles of one XCD (ids congruent
-//    mod 8) walk a contiguous range of weight-row tiles with the state-row tile
-//    varying fastest: workgroups that share weights run together on one L2.
+//    into registers (A operand of v_mfma_f32_16x16x32_bf16); states (B operand)
+//    are staged through LDS (they are stored in fragment order already, so the
+//    copy is linear and the reads are conflict-free).  Global loads run PD
+//    K-slabs ahead of the matrix cores through rotating register sets;
+//  * a workgroup is persistent over a contiguous RANGE of weight-row tiles for
+//    its block of state rows.  That is what makes the fused epilogue cheap: every
+//    lane carries, per state row, a running (max, sum-exp) and a short sorted
+//    top-k list across the tiles of its range, so a new logit costs one exp and
+//    one compare against the lane's current k-th best (insertions become rare
+//    after the first tile).  Logits are never written to memory.  The lists of
+//    the 16 lanes that share a row are merged once, when the range is done;
+//  * the next stage's projection rides in the same launch: its tiles follow the
+//    head's in the tile list (store epilogue);
+//  * workgroup ids are remapped so that the workgroups of one XCD (ids congruent
+//    mod 8) share ranges with the state-row block varying fastest: workgroups
+//    that stream the same weights run together on one L2.
 #include <hip/hip_ext.h>
 
 #include <cstring>
@@ -27,72 +32,94 @@
 
 namespace specdraft {
 
-constexpr int KS = 2;   // K-steps (of 32) per slab
-constexpr int PD = 3;   // slabs of global loads in flight ahead of the matrix cores
-constexpr int NSET = PD + 1;
+// Slab geometry per instantiation: KS K-steps (of 32) per slab, PD slabs of global
+// loads in flight ahead of the matrix cores, NSET = PD + 1 rotating register sets.
+// (Measured on the 960-row head: 4-step slabs one deep are slower than 2-step slabs two deep.)
+constexpr int slab_ks(int) { return 2; }
+constexpr int slab_pd(int) { return 2; }
 
-GemmPlan plan_gemm(int R, int n_rows_weight) {
-  GemmPlan pl;
-  if (R <= 32) { pl.mi = 2; pl.ni = 1; }
-  else if (R <= 64) { pl.mi = 4; pl.ni = 1; }
-  else { pl.mi = 8; pl.ni = 4; }
+static void fill_plan(GemmPlan& pl, int R, int n_head, int n_proj, int n_cu) {
   pl.m_tiles = (R + 16 * pl.mi - 1) / (16 * pl.mi);
-  pl.n_tiles = (n_rows_weight + 64 * pl.ni - 1) / (64 * pl.ni);
+  const int nt_head = (n_head + 64 * pl.ni - 1) / (64 * pl.ni);
+  const int nt_proj = (n_proj + 64 * pl.ni - 1) / (64 * pl.ni);
+  const int total = nt_head + nt_proj;
+  // narrow blocks are bandwidth-bound and light on registers: two workgroups per CU keep more loads in flight
+  int nr = (pl.mi <= 4 ? 2 : 1) * (n_cu > 0 ? n_cu : 256) / pl.m_tiles;
+  if (nr < 1) nr = 1;
+  if (nr > total) nr = total;
+  pl.n_ranges = nr;
+  // ranges are the balanced split t0(r) = r * total / nr; those that start inside the head hold head tiles
+  int np = 0;
+  while (np < nr && (int64_t)np * total / nr < nt_head) ++np;
+  pl.nparts = np;
+}
+
+GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
+  GemmPlan pl;
+  if (R <= 32) { pl.mi = 2; pl.ni = 1; pl.kcap = 8; }
+  else if (R <= 64 || k_top > 4 || kt % slab_ks(8) != 0) { pl.mi = 4; pl.ni = 1; pl.kcap = 8; }  // wide blocks: K % 128 == 0
+  else {
+    // state-row block of 96 or 128 rows: the one whose busiest workgroup does the least
+    // matrix-core work (tiles of its range x rows of its block)
+    pl.ni = 4;
+    pl.kcap = k_top <= 2 ? 2 : 4;
+    int64_t best_cost = -1;
+    int best = 8;
+    for (int mi : {8, 6}) {
+      GemmPlan c = pl;
+      c.mi = mi;
+      fill_plan(c, R, n_head, n_proj, n_cu);
+      const int total = (n_head + 255) / 256 + (n_proj + 255) / 256;
+      const int64_t cost = (int64_t)((total + c.n_ranges - 1) / c.n_ranges) * mi;
+      if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = mi; }
+    }
+    pl.mi = best;
+  }
+  fill_plan(pl, R, n_head, n_proj, n_cu);
   return pl;
 }
 
-// Up to two weight matrices share one launch (head, then the next stage's
-// projection): their workgroup tiles form one list, so the small projection
-// fills the tail of the head's last wave of workgroups instead of a launch of its own.
 struct GemmArgs {
-  const u32x4* w[2];  // packed weights
+  const u32x4* w[2];  // packed weights: matrix 0 = head (or the only matrix), 1 = projection
   int nt_total[2];    // 16-row tiles of each weight matrix
   int n_valid[2];     // valid weight rows
   int n_tiles[2];     // workgroup tiles along the weight rows
-  float* out[2];      // store epilogue target (matrix 0: only if mode0 == 1)
+  float* out[2];      // store epilogue target
   int64_t ldo[2];
   int mode0;          // matrix 0: 0 = top-k partials, 1 = store.  Matrix 1 always stores.
   int kt;
   const u32x4* b;     // packed states
   int R, mt_total;
-  int m_tiles, chunk; // chunk = workgroup tiles per XCD
+  int m_tiles, n_ranges, chunk;  // chunk = workgroups per XCD
   int k_top;
   Partials part;
   int nparts;
 };
 
-template <int MI, int NI>
+template <int MI, int NI, int KT>
 __global__ __launch_bounds__(256) void head_gemm_kernel(GemmArgs p) {
+  constexpr int KS = slab_ks(MI), PD = slab_pd(MI), NSET = PD + 1;
   extern __shared__ __align__(16) unsigned char smem[];
-  u32x4* ldsB = reinterpret_cast<u32x4*>(smem);  // [2][MI*KS*64]
+  u32x4* ldsB = reinterpret_cast<u32x4*>(smem);  // [NSET][MI*KS*64]
   constexpr int SLAB = MI * KS * 64;             // slots per slab
   constexpr int SPT = SLAB / 256;                // staging slots per thread
   static_assert(SLAB % 256 == 0, "a slab is staged by whole passes of the workgroup");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 15, grp = lane >> 4;
 
-  // XCD-aware tile id: hardware places workgroup ids round-robin over 8 XCDs
+  // XCD-aware workgroup id: hardware places workgroup ids round-robin over 8 XCDs
   const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
   if (seq >= p.chunk) return;
-  const int tile_id = xcd * p.chunk + seq;
-  if (tile_id >= p.m_tiles * (p.n_tiles[0] + p.n_tiles[1])) return;
-  int ntile = tile_id / p.m_tiles;
-  const int mtile = tile_id - ntile * p.m_tiles;
-  const int mat = ntile >= p.n_tiles[0] ? 1 : 0;
-  ntile -= mat ? p.n_tiles[0] : 0;
-  const int mode = mat ? 1 : p.mode0;
-  const int n_valid = p.n_valid[mat];
+  const int wg = xcd * p.chunk + seq;
+  if (wg >= p.m_tiles * p.n_ranges) return;
+  const int range = wg / p.m_tiles, mtile = wg - range * p.m_tiles;
+  const int total_tiles = p.n_tiles[0] + p.n_tiles[1];
+  const int t0 = (int)((int64_t)range * total_tiles / p.n_ranges);
+  const int t1 = (int)((int64_t)(range + 1) * total_tiles / p.n_ranges);
 
   const int kt = p.kt;
-  // weight fragments of this wave
-  const u32x4* wptr[NI];
-  int nt[NI];
-#pragma unroll
-  for (int ni = 0; ni < NI; ++ni) {
-    nt[ni] = (ntile * 4 + wave) * NI + ni;
-    const int ntc = min(nt[ni], p.nt_total[mat] - 1);
-    wptr[ni] = p.w[mat] + (int64_t)ntc * kt * 64 + lane;
-  }
-  // staging sources of this thread
+  const int nslab = kt / KS;
+  // staging sources of this thread (the same for every tile of the range)
   const u32x4* sptr[SPT];
 #pragma unroll
   for (int s = 0; s < SPT; ++s) {
@@ -102,18 +129,20 @@ __global__ __launch_bounds__(256) void head_gemm_kernel(GemmArgs p) {
     sptr[s] = p.b + (int64_t)mt * kt * 64 + rem;
   }
 
-  f32x4 acc[MI][NI];
+  // weight fragment pointers of this wave for a given tile of the list
+  const u32x4* wptr[NI];
+  auto set_tile = [&](int t, const u32x4* (&wp)[NI], int (&ntv)[NI], int& mat) {
+    mat = t >= p.n_tiles[0] ? 1 : 0;
+    const int ntile = t - (mat ? p.n_tiles[0] : 0);
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int ni = 0; ni < NI; ++ni) {
+      ntv[ni] = (ntile * 4 + wave) * NI + ni;
+      const int ntc = min(ntv[ni], p.nt_total[mat] - 1);
+      wp[ni] = p.w[mat] + (int64_t)ntc * kt * 64 + lane;
+    }
+  };
 
-  // Software pipeline over K-slabs.  Global loads (weight fragments into register
-  // set a[], state slots into register set g[]) run PD slabs ahead; a state slab
-  // is moved from its registers to LDS one slab before it is needed (LDS double
-  // buffer, one barrier per slab).  NSET = PD + 1 register sets rotate through a
-  // loop unrolled NSET times, so every index below is a compile-time constant.
-  const int nslab = kt / KS;
+  // Rotating register sets: weight fragments a[], state slots g[].
   u32x4 a[NSET][NI][KS], g[NSET][SPT];
   auto load_slab = [&](u32x4 (&aw)[NI][KS], u32x4 (&gs)[SPT], int sl) {
     const int64_t off = (int64_t)sl * KS * 64;
@@ -128,163 +157,246 @@ __global__ __launch_bounds__(256) void head_gemm_kernel(GemmArgs p) {
 #pragma unroll
     for (int s = 0; s < SPT; ++s) ldsB[buf * SLAB + s * 256 + tid] = gs[s];
   };
-  auto compute = [&](const u32x4 (&aw)[NI][KS], int buf) {
-#pragma unroll
-    for (int ts = 0; ts < KS; ++ts) {
-      u32x4 bf[MI];
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi) bf[mi] = ldsB[buf * SLAB + (mi * KS + ts) * 64 + lane];
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, aw[ni][ts]),
-                                                                __builtin_bit_cast(bf16x8, bf[mi]), acc[mi][ni], 0, 0, 0);
-    }
-  };
 
+  // running softmax / top-k state of this lane, per state row (mi, col)
+  float run_m[MI], run_s[MI], lv[MI][KT];
+  int32_t li[MI][KT];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) {
+    run_m[mi] = SPEC_NEG_INF;
+    run_s[mi] = 0.f;
+#pragma unroll
+    for (int q = 0; q < KT; ++q) { lv[mi][q] = SPEC_NEG_INF; li[mi][q] = kIdxNone; }
+  }
+  bool any_head = false;
+
+  int nt[NI], mat = 0;
+  set_tile(t0, wptr, nt, mat);
 #pragma unroll
   for (int q = 0; q < PD; ++q)
     if (q < nslab) load_slab(a[q], g[q], q);
-  store_s(g[0], 0);
-  __syncthreads();
-  for (int base = 0; base < nslab; base += NSET) {
+
+  for (int t = t0; t < t1; ++t) {
+    f32x4 acc[MI][NI];
 #pragma unroll
-    for (int u = 0; u < NSET; ++u) {
-      const int sl = base + u;
-      if (sl < nslab) {
-        if (sl + PD < nslab) load_slab(a[(u + PD) % NSET], g[(u + PD) % NSET], sl + PD);
-        compute(a[u], u & 1);
-        if (sl + 1 < nslab) store_s(g[(u + 1) % NSET], (u + 1) & 1);
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    auto compute = [&](const u32x4 (&aw)[NI][KS], int buf) {
+#pragma unroll
+      for (int ts = 0; ts < KS; ++ts) {
+        u32x4 bf[MI];
+#pragma unroll
+#ifdef SPEC_EXP_NO_LDSREAD
+        for (int mi = 0; mi < MI; ++mi) bf[mi] = aw[mi % NI][ts];
+#else
+        for (int mi = 0; mi < MI; ++mi) bf[mi] = ldsB[buf * SLAB + (mi * KS + ts) * 64 + lane];
+#endif
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int mi = 0; mi < MI; ++mi)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, aw[ni][ts]),
+                                                                  __builtin_bit_cast(bf16x8, bf[mi]), acc[mi][ni], 0, 0, 0);
+      }
+    };
+
+    // ---- K loop.  A state slab moves from its registers to LDS one slab before
+    // it is needed (one barrier per slab).  NSET register sets and NSET LDS
+    // buffers rotate through a loop unrolled NSET times (slab sl uses set and
+    // buffer sl % NSET): every index is a constant.
+    store_s(g[0], 0);
+    __syncthreads();
+    int base = 0;
+    // steady state: no branches inside, so the compiler's wait counters see
+    // straight-line code and let all PD slabs of loads stay in flight
+    for (; base + NSET + PD <= nslab; base += NSET) {
+#pragma unroll
+      for (int u = 0; u < NSET; ++u) {
+#ifndef SPEC_EXP_NO_GLOAD
+        load_slab(a[(u + PD) % NSET], g[(u + PD) % NSET], base + u + PD);
+#endif
+        compute(a[u], u);
+#ifndef SPEC_EXP_NO_LDSWRITE
+        store_s(g[(u + 1) % NSET], (u + 1) % NSET);
+#endif
+#ifndef SPEC_EXP_NO_BARRIER
         __syncthreads();
+#endif
       }
     }
-  }
-
-  // ------------------------------------------------------------------ epilogue
-  const int col = lane & 15, grp = lane >> 4;
-  if (mode == 1) {
+    // tail (at most NSET + PD - 1 slabs): the same steps, guarded
+    for (; base < nslab; base += NSET) {
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-      const int r = (mtile * MI + mi) * 16 + col;
-      if (r >= p.R) continue;
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni) {
-        const int v0 = nt[ni] * 16 + grp * 4;
-        float* o = p.out[mat] + (int64_t)r * p.ldo[mat] + v0;
-        if (v0 + 3 < n_valid && (p.ldo[mat] & 3) == 0) {
-          *reinterpret_cast<float4*>(o) = make_float4(acc[mi][ni][0], acc[mi][ni][1], acc[mi][ni][2], acc[mi][ni][3]);
-        } else {
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (v0 + i < n_valid) o[i] = acc[mi][ni][i];
+      for (int u = 0; u < NSET; ++u) {
+        const int sl = base + u;
+        if (sl < nslab) {
+          if (sl + PD < nslab) load_slab(a[(u + PD) % NSET], g[(u + PD) % NSET], sl + PD);
+          compute(a[u], u);
+          if (sl + 1 < nslab) store_s(g[(u + 1) % NSET], (u + 1) % NSET);
+          __syncthreads();
         }
       }
     }
-    return;
-  }
 
-  // top-k partials.  LDS scratch (aliases the slabs; the main loop ended on a barrier):
-  //   sv/si [4 waves][16*MI rows][k_top], sm/ss [4][16*MI]
-  const int k_top = p.k_top;
-  constexpr int ROWS = 16 * MI;
-  float* sv = reinterpret_cast<float*>(smem);
-  int32_t* si = reinterpret_cast<int32_t*>(sv + 4 * ROWS * kMaxTopK);
-  float* sm = reinterpret_cast<float*>(si + 4 * ROWS * kMaxTopK);
-  float* ss = sm + 4 * ROWS;
+    // ---- the next tile's first slabs are requested before the epilogue runs
+    const int cur_mat = mat;
+    int cur_nt[NI];
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi) {
-    // this lane's 4*NI logits of state row (mi, col), in increasing vocabulary order
-    float x[NI * 4];
-    int32_t vx[NI * 4];
+    for (int ni = 0; ni < NI; ++ni) cur_nt[ni] = nt[ni];
+    if (t + 1 < t1) {
+      set_tile(t + 1, wptr, nt, mat);
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int v = nt[ni] * 16 + grp * 4 + i;
-        vx[ni * 4 + i] = v;
-        x[ni * 4 + i] = v < n_valid ? acc[mi][ni][i] : SPEC_NEG_INF;
-      }
-    float lastv = __builtin_huge_valf();
-    int32_t lasti = -1;
-    float mx = SPEC_NEG_INF;
-    const int rl = mi * 16 + col;
-    for (int j = 0; j < k_top; ++j) {
-      float bv = SPEC_NEG_INF;
-      int32_t bi = kIdxNone;
-#pragma unroll
-      for (int e = 0; e < NI * 4; ++e)
-        if (before(lastv, lasti, x[e], vx[e]) && before(x[e], vx[e], bv, bi)) { bv = x[e]; bi = vx[e]; }
-#pragma unroll
-      for (int o = 32; o >= 16; o >>= 1) {
-        const float ov = __shfl_xor(bv, o, 64);
-        const int32_t oi = __shfl_xor(bi, o, 64);
-        if (before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-      }
-      if (j == 0) mx = bv;
-      if (grp == 0) {
-        sv[(wave * ROWS + rl) * kMaxTopK + j] = bv;
-        si[(wave * ROWS + rl) * kMaxTopK + j] = bi;
-      }
-      lastv = bv;
-      lasti = bi;
+      for (int q = 0; q < PD; ++q)
+        if (q < nslab) load_slab(a[q], g[q], q);
     }
-    float s = 0.f;
-    if (mx > SPEC_NEG_INF) {
+
+    // ---- epilogue of tile t
+    const int n_valid = p.n_valid[cur_mat];
+    if (cur_mat == 1 || p.mode0 == 1) {
 #pragma unroll
-      for (int e = 0; e < NI * 4; ++e) s += __expf(x[e] - mx);
-    }
-    s += __shfl_xor(s, 16, 64);
-    s += __shfl_xor(s, 32, 64);
-    if (grp == 0) {
-      sm[wave * ROWS + rl] = mx;
-      ss[wave * ROWS + rl] = s;
-    }
-  }
-  __syncthreads();
-  if (tid < ROWS) {
-    const int r = mtile * ROWS + tid;
-    if (r < p.R) {
-      float mx = sm[tid];
+      for (int mi = 0; mi < MI; ++mi) {
+        const int r = (mtile * MI + mi) * 16 + col;
+        if (r >= p.R) continue;
 #pragma unroll
-      for (int w = 1; w < 4; ++w) mx = fmaxf(mx, sm[w * ROWS + tid]);
-      float s = 0.f;
+        for (int ni = 0; ni < NI; ++ni) {
+          const int v0 = cur_nt[ni] * 16 + grp * 4;
+          float* o = p.out[cur_mat] + (int64_t)r * p.ldo[cur_mat] + v0;
+          if (v0 + 3 < n_valid && (p.ldo[cur_mat] & 3) == 0) {
+            *reinterpret_cast<float4*>(o) = make_float4(acc[mi][ni][0], acc[mi][ni][1], acc[mi][ni][2], acc[mi][ni][3]);
+          } else {
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const float m = sm[w * ROWS + tid];
-        if (m > SPEC_NEG_INF) s += ss[w * ROWS + tid] * __expf(m - mx);
-      }
-      const int64_t slot = (int64_t)r * p.nparts + ntile;
-      p.part.m[slot] = mx;
-      p.part.s[slot] = s;
-      int ptr[4] = {0, 0, 0, 0};
-      for (int j = 0; j < k_top; ++j) {
-        float bv = SPEC_NEG_INF;
-        int32_t bi = kIdxNone;
-        int bw = 0;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          if (ptr[w] < k_top) {
-            const float v = sv[(w * ROWS + tid) * kMaxTopK + ptr[w]];
-            const int32_t i = si[(w * ROWS + tid) * kMaxTopK + ptr[w]];
-            if (before(v, i, bv, bi)) { bv = v; bi = i; bw = w; }
+            for (int i = 0; i < 4; ++i)
+              if (v0 + i < n_valid) o[i] = acc[mi][ni][i];
           }
         }
-#pragma unroll
-        for (int w = 0; w < 4; ++w)
-          if (w == bw) ptr[w]++;
-        p.part.val[slot * k_top + j] = bv;
-        p.part.idx[slot * k_top + j] = bi;
       }
+    } else {
+      any_head = true;
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        // this lane's 4*NI logits of state row (mi, col), in increasing vocabulary order
+        float x[NI * 4];
+        float tmax = SPEC_NEG_INF;
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int v = cur_nt[ni] * 16 + grp * 4 + i;
+            const float xv = v < n_valid ? acc[mi][ni][i] : SPEC_NEG_INF;
+            x[ni * 4 + i] = xv;
+            tmax = fmaxf(tmax, xv);
+          }
+        const float new_m = fmaxf(run_m[mi], tmax);
+        if (new_m > SPEC_NEG_INF) {
+          float s = run_s[mi] * __expf(run_m[mi] - new_m);
+#pragma unroll
+          for (int e = 0; e < NI * 4; ++e) s += __expf(x[e] - new_m);
+          run_s[mi] = s;
+          run_m[mi] = new_m;
+        }
+        if (tmax > lv[mi][KT - 1]) {   // rare once the list has warmed up
+#pragma unroll
+          for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float xv = x[ni * 4 + i];
+              if (xv > lv[mi][KT - 1]) {
+                // a later vocabulary entry of equal value loses the tie: strict compares
+                float cv = xv;
+                int32_t ci = cur_nt[ni] * 16 + grp * 4 + i;
+#pragma unroll
+                for (int q = 0; q < KT; ++q) {
+                  const bool gt = cv > lv[mi][q];
+                  const float ov = lv[mi][q];
+                  const int32_t oi = li[mi][q];
+                  lv[mi][q] = gt ? cv : ov;
+                  li[mi][q] = gt ? ci : oi;
+                  cv = gt ? ov : cv;
+                  ci = gt ? oi : ci;
+                }
+              }
+            }
+        }
+      }
+    }
+  }
+
+  if (!any_head) return;
+
+  // ---- merge the 16 lane lists of every row (4 column groups x 4 waves) into the
+  // workgroup's partial.  LDS aliases the slabs: the K loop ended on a barrier.
+  constexpr int ROWS = 16 * MI;
+  float* sv = reinterpret_cast<float*>(smem);                  // [256][MI][KT]
+  int32_t* si = reinterpret_cast<int32_t*>(sv + 256 * MI * KT);
+  float* sm = reinterpret_cast<float*>(si + 256 * MI * KT);    // [256][MI]
+  float* ss = sm + 256 * MI;
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+    for (int q = 0; q < KT; ++q) {
+      sv[(tid * MI + mi) * KT + q] = lv[mi][q];
+      si[(tid * MI + mi) * KT + q] = li[mi][q];
+    }
+    sm[tid * MI + mi] = run_m[mi];
+    ss[tid * MI + mi] = run_s[mi];
+  }
+  __syncthreads();
+  for (int rl = tid; rl < ROWS; rl += 256) {
+    const int r = mtile * ROWS + rl;
+    if (r >= p.R) continue;
+    const int mi = rl >> 4, c = rl & 15;
+    float mx = SPEC_NEG_INF;
+    for (int src = 0; src < 16; ++src) mx = fmaxf(mx, sm[((src >> 2) * 64 + (src & 3) * 16 + c) * MI + mi]);
+    float s = 0.f;
+    for (int src = 0; src < 16; ++src) {
+      const int th = (src >> 2) * 64 + (src & 3) * 16 + c;
+      const float m = sm[th * MI + mi];
+      if (m > SPEC_NEG_INF) s += ss[th * MI + mi] * __expf(m - mx);
+    }
+    const int64_t slot = (int64_t)r * p.nparts + range;
+    p.part.m[slot] = mx;
+    p.part.s[slot] = s;
+    float lastv = __builtin_huge_valf();
+    int32_t lasti = -1;
+    for (int j = 0; j < p.k_top; ++j) {
+      float bv = SPEC_NEG_INF;
+      int32_t bi = kIdxNone;
+      for (int src = 0; src < 16; ++src) {
+        const int th = (src >> 2) * 64 + (src & 3) * 16 + c;
+#pragma unroll
+        for (int q = 0; q < KT; ++q) {
+          const float v = sv[(th * MI + mi) * KT + q];
+          const int32_t i = si[(th * MI + mi) * KT + q];
+          if (before(lastv, lasti, v, i) && before(v, i, bv, bi)) { bv = v; bi = i; }
+        }
+      }
+      p.part.val[slot * p.k_top + j] = bv;
+      p.part.idx[slot * p.k_top + j] = bi;
+      lastv = bv;
+      lasti = bi;
     }
   }
 }
 
-static size_t gemm_smem(int mi) {
-  const size_t slabs = (size_t)2 * mi * KS * 64 * 16;
-  const size_t rows = 16 * (size_t)mi;
-  const size_t epi = 4 * rows * kMaxTopK * 8 + 4 * rows * 8;
-  return slabs > epi ? slabs : epi;
+static size_t gemm_smem(int mi, int kcap) {
+  const size_t slabs = (size_t)(slab_pd(mi) + 1) * mi * slab_ks(mi) * 64 * 16;
+  const size_t merge = (size_t)256 * mi * (kcap * 8 + 8);
+  return slabs > merge ? slabs : merge;
+}
+
+template <int MI, int NI, int KT>
+static hipError_t launch_gemm_t(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
+  const size_t smem = gemm_smem(MI, KT);
+  static bool attr_set = false;  // per instantiation
+  if (!attr_set && smem > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_gemm_kernel<MI, NI, KT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipExtLaunchKernelGGL((head_gemm_kernel<MI, NI, KT>), dim3(a.chunk * 8), dim3(256), smem, st, ev_start, ev_stop, 0, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t st, hipEvent_t ev_start,
@@ -303,13 +415,13 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
     ++nm;
   }
   if (job.vt_proj > 0) {
+    if (nm == 0) a.mode0 = 1;  // projection alone: it is matrix 0 with the store epilogue
     a.w[nm] = static_cast<const u32x4*>(job.w_proj);
     a.nt_total[nm] = job.vt_proj;
     a.n_valid[nm] = job.n_proj;
     a.n_tiles[nm] = (job.n_proj + 64 * pl.ni - 1) / (64 * pl.ni);
     a.out[nm] = job.out_proj;
     a.ldo[nm] = job.ld_proj;
-    if (nm == 0) a.mode0 = 1;
     ++nm;
   }
   if (nm == 0) return hipErrorInvalidValue;
@@ -318,18 +430,22 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
   a.R = job.R;
   a.mt_total = (job.R + 15) / 16;
   a.m_tiles = pl.m_tiles;
-  const int total = pl.m_tiles * (a.n_tiles[0] + a.n_tiles[1]);
-  a.chunk = (total + 7) / 8;
+  a.n_ranges = pl.n_ranges;
+  a.chunk = (pl.m_tiles * pl.n_ranges + 7) / 8;
   a.k_top = job.k_top;
   a.part = job.part;
   a.nparts = job.nparts;
-  dim3 grid(a.chunk * 8), block(256);
-  const size_t smem = gemm_smem(pl.mi);
-  if (pl.mi == 2 && pl.ni == 1) hipExtLaunchKernelGGL((head_gemm_kernel<2, 1>), grid, block, smem, st, ev_start, ev_stop, 0, a);
-  else if (pl.mi == 4 && pl.ni == 1) hipExtLaunchKernelGGL((head_gemm_kernel<4, 1>), grid, block, smem, st, ev_start, ev_stop, 0, a);
-  else if (pl.mi == 8 && pl.ni == 4) hipExtLaunchKernelGGL((head_gemm_kernel<8, 4>), grid, block, smem, st, ev_start, ev_stop, 0, a);
-  else return hipErrorInvalidValue;
-  return hipGetLastError();
+  if (a.mode0 == 0 && job.k_top > pl.kcap) return hipErrorInvalidValue;
+  const int key = pl.mi * 100 + pl.ni * 10 + pl.kcap;
+  switch (key) {
+    case 2 * 100 + 1 * 10 + 8: return launch_gemm_t<2, 1, 8>(a, st, ev_start, ev_stop);
+    case 4 * 100 + 1 * 10 + 8: return launch_gemm_t<4, 1, 8>(a, st, ev_start, ev_stop);
+    case 6 * 100 + 4 * 10 + 2: return launch_gemm_t<6, 4, 2>(a, st, ev_start, ev_stop);
+    case 6 * 100 + 4 * 10 + 4: return launch_gemm_t<6, 4, 4>(a, st, ev_start, ev_stop);
+    case 8 * 100 + 4 * 10 + 2: return launch_gemm_t<8, 4, 2>(a, st, ev_start, ev_stop);
+    case 8 * 100 + 4 * 10 + 4: return launch_gemm_t<8, 4, 4>(a, st, ev_start, ev_stop);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 }  // namespace specdraft

@@ -73,13 +73,18 @@ int skinny_grid(int n_cu);
 hipError_t launch_head_skinny(const HeadJob& job, int n_cu, hipStream_t st, hipEvent_t ev_start = nullptr,
                               hipEvent_t ev_stop = nullptr);
 
-// Any number of rows: workgroup tiles of (16*MI rows) x (64*NI weight rows).
-// Head (top-k partials or store) and, if present, the projection (store) in one launch.
+// Any number of rows: workgroups of (16*mi state rows) x (64*ni weight rows) tiles, each
+// persistent over one of n_ranges contiguous ranges of the weight-row tiles.  Head
+// (top-k partials, one part per range that holds head tiles; or store) and, if present,
+// the projection (store) in one launch.
 struct GemmPlan {
-  int mi, ni;       // fragments per wave in M (state rows) and N (weight rows)
-  int m_tiles, n_tiles;
+  int mi, ni;        // fragments per wave in M (state rows) and N (weight rows)
+  int kcap;          // capacity of the per-lane top-k lists (>= k_top)
+  int m_tiles;       // blocks of state rows
+  int n_ranges;      // ranges of weight-row tiles
+  int nparts;        // ranges that hold head tiles = parts per row
 };
-GemmPlan plan_gemm(int R, int n_rows_weight);
+GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu);
 hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& plan, hipStream_t st, hipEvent_t ev_start = nullptr,
                             hipEvent_t ev_stop = nullptr);
 

@@ -124,16 +124,15 @@ static spec_status_t check_config(const spec_config_t* c) {
   return SPEC_OK;
 }
 
-// capacity (in (row, part) slots) that covers every contraction plan a call may pick
+// capacity (in (row, part) slots) that covers every contraction plan a call may pick:
+// the streaming kernel writes one part per workgroup (one per CU), the dense kernel at
+// most one per range (<= one per CU, two for blocks of <= 64 rows), the float32 path one per row
 static int64_t partial_capacity(int64_t max_rows, int V, int n_cu) {
+  (void)V;
+  const int64_t cus = n_cu > 0 ? n_cu : 256;
   int64_t cap = 16 * (int64_t)skinny_grid(n_cu);
-  for (int64_t R : {(int64_t)32, (int64_t)64, max_rows}) {
-    const int64_t r = R < max_rows ? R : max_rows;
-    GemmPlan pl = plan_gemm((int)r, V);
-    const int64_t c = r * pl.n_tiles;
-    if (c > cap) cap = c;
-  }
-  if (max_rows > cap) cap = max_rows;  // f32 path: one part per row
+  if (64 * 2 * cus > cap) cap = 64 * 2 * cus;        // narrow blocks (<= 64 rows): up to two ranges per CU
+  if (max_rows * cus > cap) cap = max_rows * cus;
   return cap;
 }
 
@@ -352,14 +351,11 @@ static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, c
     job.b_src = m->state_in;
     job.b_rowmajor = 0;
   }
-  *nparts = 1;
-  GemmPlan pl = plan_gemm(R, stage >= 0 ? V : D);
-  if (stage >= 0) {
-    job.nparts = pl.n_tiles;
-    *nparts = pl.n_tiles;
-    if (!out_head && (int64_t)R * pl.n_tiles > m->part_rows_parts)
-      return fail(SPEC_ESHAPE, "internal: partial workspace too small (%d rows x %d parts)", R, pl.n_tiles);
-  }
+  GemmPlan pl = plan_gemm(R, k_top, job.n_head, job.n_proj, job.kt, m->n_cu);
+  job.nparts = pl.nparts > 0 ? pl.nparts : 1;
+  *nparts = job.nparts;
+  if (stage >= 0 && !out_head && (int64_t)R * job.nparts > m->part_rows_parts)
+    return fail(SPEC_ESHAPE, "internal: partial workspace too small (%d rows x %d parts)", R, job.nparts);
   const int slot = prof_slot(m, pl.mi == 2 ? 1 : (pl.mi == 4 ? 2 : 3), R, job.n_head + job.n_proj, K);
   HIP_TRY(launch_head_gemm(job, pl, st, EV0(slot), EV1(slot)));
   return SPEC_OK;
