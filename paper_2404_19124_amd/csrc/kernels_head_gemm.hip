@@ -32,11 +32,14 @@
 
 namespace specdraft {
 
-// Slab geometry per instantiation: KS K-steps (of 32) per slab, PD slabs of global
-// loads in flight ahead of the matrix cores, NSET = PD + 1 rotating register sets.
-// (Measured on the 960-row head: 4-step slabs one deep are slower than 2-step slabs two deep.)
-constexpr int slab_ks(int) { return 2; }
-constexpr int slab_pd(int) { return 2; }
+// Slab geometry: KS K-steps (of 32) per slab; global loads run PD slabs ahead of the
+// matrix cores through NSET = PD + 1 rotating register sets; a state slab is written to
+// one of NSET LDS buffers TWO slabs before it is used, so that the fragments of the next
+// slab's first K-step can be read before the barrier that closes the current slab and the
+// matrix cores never wait for LDS behind a barrier.
+constexpr int KS = 2;
+constexpr int PD = 3;
+constexpr int NSET = PD + 1;
 
 static void fill_plan(GemmPlan& pl, int R, int n_head, int n_proj, int n_cu) {
   pl.m_tiles = (R + 16 * pl.mi - 1) / (16 * pl.mi);
@@ -57,7 +60,7 @@ static void fill_plan(GemmPlan& pl, int R, int n_head, int n_proj, int n_cu) {
 GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
   GemmPlan pl;
   if (R <= 32) { pl.mi = 2; pl.ni = 1; pl.kcap = 8; }
-  else if (R <= 64 || k_top > 4 || kt % slab_ks(8) != 0) { pl.mi = 4; pl.ni = 1; pl.kcap = 8; }  // wide blocks: K % 128 == 0
+  else if (R <= 64 || k_top > 4) { pl.mi = 4; pl.ni = 1; pl.kcap = 8; }
   else {
     // state-row block of 96 or 128 rows: the one whose busiest workgroup does the least
     // matrix-core work (tiles of its range x rows of its block)
@@ -65,7 +68,7 @@ GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
     pl.kcap = k_top <= 2 ? 2 : 4;
     int64_t best_cost = -1;
     int best = 8;
-    for (int mi : {8, 6}) {
+    for (int mi : {6}) {
       GemmPlan c = pl;
       c.mi = mi;
       fill_plan(c, R, n_head, n_proj, n_cu);
@@ -96,14 +99,16 @@ struct GemmArgs {
   int nparts;
 };
 
+// Narrow blocks (MI <= 4) are bandwidth-bound: two workgroups per CU (two waves per
+// SIMD, 256 registers each) keep twice the loads in flight; wide blocks take all 512.
 template <int MI, int NI, int KT>
-__global__ __launch_bounds__(256) void head_gemm_kernel(GemmArgs p) {
-  constexpr int KS = slab_ks(MI), PD = slab_pd(MI), NSET = PD + 1;
+__global__ __launch_bounds__(256, (MI <= 4 ? 2 : 1)) void head_gemm_kernel(GemmArgs p) {
   extern __shared__ __align__(16) unsigned char smem[];
   u32x4* ldsB = reinterpret_cast<u32x4*>(smem);  // [NSET][MI*KS*64]
   constexpr int SLAB = MI * KS * 64;             // slots per slab
   constexpr int SPT = SLAB / 256;                // staging slots per thread
   static_assert(SLAB % 256 == 0, "a slab is staged by whole passes of the workgroup");
+  static_assert(KS == 2, "the K loop below is written for two K-steps per slab");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, grp = lane >> 4;
 
@@ -182,47 +187,39 @@ __global__ __launch_bounds__(256) void head_gemm_kernel(GemmArgs p) {
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    auto compute = [&](const u32x4 (&aw)[NI][KS], int buf) {
+    auto read_b = [&](u32x4 (&bf)[MI], int buf, int ts) {
 #pragma unroll
-      for (int ts = 0; ts < KS; ++ts) {
-        u32x4 bf[MI];
+      for (int mi = 0; mi < MI; ++mi) bf[mi] = ldsB[buf * SLAB + (mi * KS + ts) * 64 + lane];
+    };
+    auto mma = [&](const u32x4 (&aw)[NI][KS], const u32x4 (&bf)[MI], int ts) {
 #pragma unroll
-#ifdef SPEC_EXP_NO_LDSREAD
-        for (int mi = 0; mi < MI; ++mi) bf[mi] = aw[mi % NI][ts];
-#else
-        for (int mi = 0; mi < MI; ++mi) bf[mi] = ldsB[buf * SLAB + (mi * KS + ts) * 64 + lane];
-#endif
+      for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-          for (int mi = 0; mi < MI; ++mi)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, aw[ni][ts]),
-                                                                  __builtin_bit_cast(bf16x8, bf[mi]), acc[mi][ni], 0, 0, 0);
-      }
+        for (int mi = 0; mi < MI; ++mi)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, aw[ni][ts]),
+                                                                __builtin_bit_cast(bf16x8, bf[mi]), acc[mi][ni], 0, 0, 0);
     };
 
-    // ---- K loop.  A state slab moves from its registers to LDS one slab before
-    // it is needed (one barrier per slab).  NSET register sets and NSET LDS
-    // buffers rotate through a loop unrolled NSET times (slab sl uses set and
-    // buffer sl % NSET): every index is a constant.
+    // ---- K loop (slab sl uses register set and LDS buffer sl % NSET; the loop is
+    // unrolled NSET times so every index is a constant)
     store_s(g[0], 0);
+    if (nslab > 1) store_s(g[1], 1);
     __syncthreads();
+    u32x4 bf0[MI], bf1[MI];
+    read_b(bf0, 0, 0);
     int base = 0;
     // steady state: no branches inside, so the compiler's wait counters see
     // straight-line code and let all PD slabs of loads stay in flight
     for (; base + NSET + PD <= nslab; base += NSET) {
 #pragma unroll
       for (int u = 0; u < NSET; ++u) {
-#ifndef SPEC_EXP_NO_GLOAD
         load_slab(a[(u + PD) % NSET], g[(u + PD) % NSET], base + u + PD);
-#endif
-        compute(a[u], u);
-#ifndef SPEC_EXP_NO_LDSWRITE
-        store_s(g[(u + 1) % NSET], (u + 1) % NSET);
-#endif
-#ifndef SPEC_EXP_NO_BARRIER
+        read_b(bf1, u, 1);
+        mma(a[u], bf0, 0);
+        store_s(g[(u + 2) % NSET], (u + 2) % NSET);
+        mma(a[u], bf1, 1);
+        read_b(bf0, (u + 1) % NSET, 0);
         __syncthreads();
-#endif
       }
     }
     // tail (at most NSET + PD - 1 slabs): the same steps, guarded
@@ -232,8 +229,11 @@ __global__ __launch_bounds__(256) void head_gemm_kernel(GemmArgs p) {
         const int sl = base + u;
         if (sl < nslab) {
           if (sl + PD < nslab) load_slab(a[(u + PD) % NSET], g[(u + PD) % NSET], sl + PD);
-          compute(a[u], u);
-          if (sl + 1 < nslab) store_s(g[(u + 1) % NSET], (u + 1) % NSET);
+          read_b(bf1, u, 1);
+          mma(a[u], bf0, 0);
+          if (sl + 2 < nslab) store_s(g[(u + 2) % NSET], (u + 2) % NSET);
+          mma(a[u], bf1, 1);
+          if (sl + 1 < nslab) read_b(bf0, (u + 1) % NSET, 0);
           __syncthreads();
         }
       }
@@ -357,30 +357,30 @@ __global__ __launch_bounds__(256) void head_gemm_kernel(GemmArgs p) {
     const int64_t slot = (int64_t)r * p.nparts + range;
     p.part.m[slot] = mx;
     p.part.s[slot] = s;
-    float lastv = __builtin_huge_valf();
-    int32_t lasti = -1;
+    // 16-way merge of sorted lists: only the heads compete; 4-bit read positions packed in one word
+    uint64_t pos = 0;
     for (int j = 0; j < p.k_top; ++j) {
       float bv = SPEC_NEG_INF;
       int32_t bi = kIdxNone;
+      int bsrc = 0;
       for (int src = 0; src < 16; ++src) {
-        const int th = (src >> 2) * 64 + (src & 3) * 16 + c;
-#pragma unroll
-        for (int q = 0; q < KT; ++q) {
+        const int q = (int)((pos >> (4 * src)) & 15);
+        if (q < KT) {
+          const int th = (src >> 2) * 64 + (src & 3) * 16 + c;
           const float v = sv[(th * MI + mi) * KT + q];
           const int32_t i = si[(th * MI + mi) * KT + q];
-          if (before(lastv, lasti, v, i) && before(v, i, bv, bi)) { bv = v; bi = i; }
+          if (before(v, i, bv, bi)) { bv = v; bi = i; bsrc = src; }
         }
       }
+      pos += (uint64_t)1 << (4 * bsrc);
       p.part.val[slot * p.k_top + j] = bv;
       p.part.idx[slot * p.k_top + j] = bi;
-      lastv = bv;
-      lasti = bi;
     }
   }
 }
 
 static size_t gemm_smem(int mi, int kcap) {
-  const size_t slabs = (size_t)(slab_pd(mi) + 1) * mi * slab_ks(mi) * 64 * 16;
+  const size_t slabs = (size_t)NSET * mi * KS * 64 * 16;
   const size_t merge = (size_t)256 * mi * (kcap * 8 + 8);
   return slabs > merge ? slabs : merge;
 }
@@ -442,8 +442,6 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
     case 4 * 100 + 1 * 10 + 8: return launch_gemm_t<4, 1, 8>(a, st, ev_start, ev_stop);
     case 6 * 100 + 4 * 10 + 2: return launch_gemm_t<6, 4, 2>(a, st, ev_start, ev_stop);
     case 6 * 100 + 4 * 10 + 4: return launch_gemm_t<6, 4, 4>(a, st, ev_start, ev_stop);
-    case 8 * 100 + 4 * 10 + 2: return launch_gemm_t<8, 4, 2>(a, st, ev_start, ev_stop);
-    case 8 * 100 + 4 * 10 + 4: return launch_gemm_t<8, 4, 4>(a, st, ev_start, ev_stop);
     default: return hipErrorInvalidValue;
   }
 }
