@@ -163,15 +163,28 @@ hipError_t launch_stage(const StageJob& job, hipStream_t st) {
 // every leaf by the sum of its tokens' log-probabilities (added in stage order),
 // keep the B best.  One workgroup per sequence.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void tree_kernel(TreeJob j) {
+// 512 threads: eight waves merge eight rows at a time, and each wave may use 256 registers (the
+// widest merge needs more than the 128 a 1024-thread workgroup would leave it).
+__global__ __launch_bounds__(512) void tree_kernel(TreeJob j) {
   __shared__ float sc[kMaxLeaves];
+  // per-stage tables of the job in LDS: indexing kernel arguments with a run-time
+  // stage number would make the compiler spill the whole argument block to scratch
+  __shared__ int s_k[kMaxStages];
+  __shared__ int64_t s_off[kMaxStages];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int q = blockIdx.x;
   const int n = j.n, L = j.L;
-  const int k_last = j.top_k[n - 1];
+  int k_last = 1;
+  int64_t off_last = 0, row_off_last = 0;
+#pragma unroll
+  for (int i = 0; i < kMaxStages; ++i) {
+    if (tid == i) { s_k[i] = j.top_k[i]; s_off[i] = j.off[i]; }
+    if (i == n - 1) { k_last = j.top_k[i]; off_last = j.off[i]; row_off_last = j.row_off[i]; }
+  }
   const int rows_last = L / k_last;
 
-  for (int rl = wave; rl < rows_last; rl += 16) {
+#ifndef SPEC_EXP_TREE_NO_MERGE
+  for (int rl = wave; rl < rows_last; rl += 8) {
     const int64_t row = (int64_t)q * rows_last + rl;
     float v[kMaxTopK];
     int32_t ix[kMaxTopK];
@@ -180,30 +193,34 @@ __global__ __launch_bounds__(1024) void tree_kernel(TreeJob j) {
 #pragma unroll
     for (int t = 0; t < kMaxTopK; ++t)
       if (lane == t && t < k_last) {
-        j.tok[j.off[n - 1] + row * k_last + t] = ix[t];
-        j.logp[j.off[n - 1] + row * k_last + t] = v[t] - lse;
+        j.tok[off_last + row * k_last + t] = ix[t];
+        j.logp[off_last + row * k_last + t] = v[t] - lse;
       }
-    if (lane == 0) j.lse[j.row_off[n - 1] + row] = lse;
+    if (lane == 0) j.lse[row_off_last + row] = lse;
   }
+#endif
   __threadfence_block();
   __syncthreads();
 
-  for (int leaf = tid; leaf < L; leaf += 1024) {
+  for (int leaf = tid; leaf < L; leaf += 512) {
     float score = 0.f;
     int64_t row = q;
     int stride = L;
     for (int i = 0; i < n; ++i) {
-      const int k = j.top_k[i];
+      const int k = s_k[i];
       stride /= k;
       const int rank = (leaf / stride) % k;
-      score += j.logp[j.off[i] + row * k + rank];
+      score += j.logp[s_off[i] + row * k + rank];
       row = row * k + rank;
     }
     sc[leaf] = score;
   }
   __syncthreads();
 
-  for (int leaf = tid; leaf < L; leaf += 1024) {
+#ifdef SPEC_EXP_TREE_NO_RANK
+  return;
+#endif
+  for (int leaf = tid; leaf < L; leaf += 512) {
     const float s = sc[leaf];
     int pos = 0;
     for (int o = 0; o < L; ++o) {
@@ -217,10 +234,10 @@ __global__ __launch_bounds__(1024) void tree_kernel(TreeJob j) {
       int64_t row = q;
       int stride = L;
       for (int i = 0; i < n; ++i) {
-        const int k = j.top_k[i];
+        const int k = s_k[i];
         stride /= k;
         const int rank = (leaf / stride) % k;
-        j.cand_tokens[c * n + i] = j.tok[j.off[i] + row * k + rank];
+        j.cand_tokens[c * n + i] = j.tok[s_off[i] + row * k + rank];
         row = row * k + rank;
       }
     }
@@ -228,7 +245,7 @@ __global__ __launch_bounds__(1024) void tree_kernel(TreeJob j) {
 }
 
 hipError_t launch_tree(const TreeJob& job, hipStream_t st) {
-  hipLaunchKernelGGL(tree_kernel, dim3(job.batch), dim3(1024), 0, st, job);
+  hipLaunchKernelGGL(tree_kernel, dim3(job.batch), dim3(512), 0, st, job);
   return hipGetLastError();
 }
 

@@ -55,15 +55,22 @@ __device__ __forceinline__ void wave_merge_partials_k(const Partials& p, int64_t
     int32_t li[UN][K];
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
+      // every load is unconditional (clamped to a valid slot) so that all of them are
+      // in flight together; what does not exist is masked after it arrives
       const int part = p0 + u * 64 + lane;
       const bool ok = part < nparts;
-      lm[u] = ok ? pm[part] : SPEC_NEG_INF;
-      ls[u] = ok ? ps[part] : 0.f;
+      const int pc = ok ? part : nparts - 1;
+      const float m_ = pm[pc], s_ = ps[pc];
+      lm[u] = ok ? m_ : SPEC_NEG_INF;
+      ls[u] = ok ? s_ : 0.f;
 #pragma unroll
       for (int j = 0; j < K; ++j) {
+        const int jc = j < k ? j : k - 1;
+        const float v_ = pv[(int64_t)pc * k + jc];
+        const int32_t i_ = pi[(int64_t)pc * k + jc];
         const bool okj = ok && j < k;
-        lv[u][j] = okj ? pv[(int64_t)part * k + j] : SPEC_NEG_INF;
-        li[u][j] = okj ? pi[(int64_t)part * k + j] : kIdxNone;
+        lv[u][j] = okj ? v_ : SPEC_NEG_INF;
+        li[u][j] = okj ? i_ : kIdxNone;
       }
     }
 #pragma unroll
