@@ -1,6 +1,7 @@
 """Benchmark of one draft + verify step on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+    python bench.py --copy-probe BYTES      (counter calibration only, see profiles/)
 
 A step = spec_draft followed by spec_verify, enqueued back to back on one
 stream, on one batch of seeded synthetic inputs that are resident in HBM before
@@ -29,8 +30,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
-KERNEL_NAMES = {0: "head_skinny_kernel", 1: "head_gemm_kernel<2,1>", 2: "head_gemm_kernel<4,1>",
-                3: "head_gemm_kernel<8,4>"}
+# labels of spec_launch_record_t.kernel (first template argument of head_gemm_kernel = 16-row
+# fragments per state block)
+KERNEL_NAMES = {0: "head_skinny_kernel", 1: "head_gemm_kernel<2,...>", 2: "head_gemm_kernel<4,...>",
+                3: "head_gemm_kernel<6,...>"}
 
 
 def main() -> int:
@@ -42,6 +45,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--verbose", action="store_true", help="per-shape timing of the contraction launches on stderr")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
+                    help="instead of the benchmark: launch the library's plain copy kernel over BYTES a few times "
+                         "(calibration of rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding in "
@@ -58,6 +64,17 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.copy_probe:
+        n = args.copy_probe // 16 * 16
+        src = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        for _ in range(5):
+            B.spec_copy_probe(src, dst, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        ok = bool(torch.equal(src, dst))
+        print(json.dumps({"copy_probe_bytes": n, "launches": 5, "copied_correctly": ok}), flush=True)
+        return 0 if ok else 1
     wl = W.WORKLOADS[args.workload]
     gen = W.make_generator(wl.seed, "cuda")
     w = W.make_speculator(wl, gen, device="cuda")
@@ -185,7 +202,12 @@ def _cpu_baseline(wl, w, state, last, logits, step, budget_s: float):
         cores = len(os.sched_getaffinity(0))
     except AttributeError:
         cores = os.cpu_count() or 1
-    threads = torch.get_num_threads()
+    # numpy's BLAS does the oracle's matmuls: its pool size is the number of threads really used
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except ImportError:
+        threads = cores
     wn = W.weights_to_numpy(w)
     nseq = min(wl.batch, 2)
     st = W.to_numpy_f32(state[:nseq])
@@ -206,8 +228,8 @@ def _cpu_baseline(wl, w, state, last, logits, step, budget_s: float):
     dt = (time.perf_counter() - t0) / reps
     # a step covers the whole batch: scale the sampled sequences up (sequences are independent)
     step_s = dt * wl.batch / nseq
-    return {"value": round(1.0 / step_s, 4), "unit": "steps/s", "cores": cores, "kind": "oracle",
-            "blas_threads": threads,
+    return {"value": round(1.0 / step_s, 4), "unit": "steps/s", "cores": min(threads, cores), "kind": "oracle",
+            "host_cores": cores,
             "sample": "%d whole draft+verify step(s) of %d of %d sequence(s), %d repetition(s), %.2f s each; "
                       "scaled by batch/sample" % (reps, nseq, wl.batch, reps, dt)}
 

@@ -158,7 +158,7 @@ spec_status_t spec_head_logp(spec_model_t* m, int32_t stage, const void* states,
  * roofline reports.  While enabled, spec_draft attaches a pair of HIP events to
  * every contraction launch (they receive that kernel's begin / end time on the
  * caller's stream); nothing else changes.
- *   kernel: 0 = rows<=16 streaming kernel, 1..3 = dense kernel with 32/64/128-row tiles
+ *   kernel: 0 = rows<=16 streaming kernel, 1..3 = dense kernel with 32/64/96-row state blocks
  *   rows, weight_rows, k: the contraction is [rows, k] x [weight_rows, k]^T
  *                  (weight_rows counts head and fused next-projection rows together)
  *   ms: elapsed time between the two events */
@@ -174,6 +174,14 @@ spec_status_t spec_profile_enable(spec_model_t* m, int32_t capacity);
 /* Waits for the recorded events, writes up to `cap` records to `out` (host) in launch
  * order, stores their number in *n (host) and clears the recording. */
 spec_status_t spec_profile_read(spec_model_t* m, spec_launch_record_t* out, int32_t cap, int32_t* n);
+
+/* Measurement aid, not a step of the method: one launch of a plain copy kernel that
+ * reads `bytes` from src (dev) and writes them to dst (dev; must not overlap src).  Its HBM
+ * traffic is known exactly, which calibrates the memory-traffic hardware counters that
+ * the roofline reports of the contraction kernels are checked against.
+ *   bytes: positive multiple of 16; src, dst 16-byte aligned; asynchronous on hip_stream.
+ * SPEC_EINVAL on bad arguments (nothing is launched). */
+spec_status_t spec_copy_probe(const void* src, void* dst, int64_t bytes, void* hip_stream);
 
 /* Reads back the mix weights and epsilon the model uses (after defaults were applied). */
 spec_status_t spec_model_scalars(const spec_model_t* m, float* state_weight, float* emb_weight,

@@ -22,7 +22,7 @@ SPEC_OK, SPEC_EINVAL, SPEC_ESHAPE, SPEC_EDTYPE, SPEC_ENOMEM, SPEC_EHIP = 0, -1, 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecdraft.so")
 
 EXPORTS = ["spec_create", "spec_destroy", "spec_draft", "spec_verify", "spec_head_logp", "spec_model_scalars",
-           "spec_profile_enable", "spec_profile_read", "spec_last_error", "spec_version"]
+           "spec_profile_enable", "spec_profile_read", "spec_copy_probe", "spec_last_error", "spec_version"]
 
 
 class SpecError(RuntimeError):
@@ -82,6 +82,8 @@ def lib() -> C.CDLL:
         l.spec_profile_enable.argtypes = [C.c_void_p, C.c_int32]
         l.spec_profile_read.restype = C.c_int
         l.spec_profile_read.argtypes = [C.c_void_p, C.POINTER(spec_launch_record_t), C.c_int32, C.POINTER(C.c_int32)]
+        l.spec_copy_probe.restype = C.c_int
+        l.spec_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         l.spec_last_error.restype = C.c_char_p
         l.spec_last_error.argtypes = []
         l.spec_version.restype = C.c_int
@@ -206,6 +208,15 @@ def spec_profile_read(model: SpecModel, cap: int = 65536):
     n = C.c_int32()
     _check(lib().spec_profile_read(model.handle, buf, cap, C.byref(n)))
     return [dict(kernel=r.kernel, rows=r.rows, weight_rows=r.weight_rows, k=r.k, ms=r.ms) for r in buf[:n.value]]
+
+
+def spec_copy_probe(src: torch.Tensor, dst: torch.Tensor, stream=None) -> int:
+    """One plain copy launch src -> dst (same byte size); returns the bytes copied."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("src and dst differ in size")
+    _check(lib().spec_copy_probe(_ptr(src), _ptr(dst), nbytes, _stream_ptr(stream)))
+    return nbytes
 
 
 def spec_head_logp(model: SpecModel, stage: int, states: torch.Tensor, logp: torch.Tensor, stream=None) -> None:

@@ -150,4 +150,19 @@ hipError_t launch_row_log_softmax(const float* logits, float* logp, int64_t ld, 
   return hipGetLastError();
 }
 
+// Plain copy of n 16-byte words, grid-stride: a launch whose HBM traffic is known
+// exactly (n * 16 bytes read, n * 16 written), used to calibrate traffic counters.
+__global__ __launch_bounds__(256) void copy_probe_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
+                                                         int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_copy_probe(const void* src, void* dst, int64_t n16, hipStream_t st) {
+  const int64_t want = (n16 + 255) / 256;
+  const int grid = (int)(want < 1 ? 1 : (want > 16384 ? 16384 : want));
+  hipLaunchKernelGGL(copy_probe_kernel, dim3(grid), dim3(256), 0, st, static_cast<const u32x4*>(src),
+                     static_cast<u32x4*>(dst), n16);
+  return hipGetLastError();
+}
+
 }  // namespace specdraft

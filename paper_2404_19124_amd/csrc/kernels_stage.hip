@@ -12,6 +12,7 @@ namespace specdraft {
 template <bool BF16, int NCH>
 __global__ __launch_bounds__(256) void stage_kernel(StageJob j) {
   __shared__ float scratch[8];
+  __shared__ float merge_lds[32];
   const int tid = threadIdx.x, lane = tid & 63;
   const int r = blockIdx.x;
   const int parent = r / j.k_prev, rank = r - parent * j.k_prev;
@@ -47,7 +48,7 @@ __global__ __launch_bounds__(256) void stage_kernel(StageJob j) {
     float v[kMaxTopK];
     int32_t ix[kMaxTopK];
     float lse;
-    wave_merge_partials(j.part, parent, j.nparts, j.k_prev, v, ix, lse);
+    block_merge_partials(j.part, parent, j.nparts, j.k_prev, v, ix, lse, merge_lds);
     tok = ix[0];
 #pragma unroll
     for (int q = 1; q < kMaxTopK; ++q)
@@ -183,7 +184,6 @@ __global__ __launch_bounds__(512) void tree_kernel(TreeJob j) {
   }
   const int rows_last = L / k_last;
 
-#ifndef SPEC_EXP_TREE_NO_MERGE
   for (int rl = wave; rl < rows_last; rl += 8) {
     const int64_t row = (int64_t)q * rows_last + rl;
     float v[kMaxTopK];
@@ -198,7 +198,6 @@ __global__ __launch_bounds__(512) void tree_kernel(TreeJob j) {
       }
     if (lane == 0) j.lse[row_off_last + row] = lse;
   }
-#endif
   __threadfence_block();
   __syncthreads();
 
@@ -217,9 +216,6 @@ __global__ __launch_bounds__(512) void tree_kernel(TreeJob j) {
   }
   __syncthreads();
 
-#ifdef SPEC_EXP_TREE_NO_RANK
-  return;
-#endif
   for (int leaf = tid; leaf < L; leaf += 512) {
     const float s = sc[leaf];
     int pos = 0;

@@ -114,6 +114,108 @@ __device__ __forceinline__ void wave_merge_partials_k(const Partials& p, int64_t
   }
 }
 
+// The same merge done by a whole 256-thread workgroup for ONE row: with at most 256
+// parts every thread holds exactly one part's (already sorted) list, so nothing has to
+// be inserted; the k results are popped with one wave reduction plus a 4-entry
+// exchange through LDS per round.  All 256 threads must call; every thread receives
+// the result.  `lds` needs 32 words.
+template <int K>
+__device__ __forceinline__ void block_merge_partials_k(const Partials& p, int64_t row, int nparts, int k,
+                                                     float (&out_val)[kMaxTopK], int32_t (&out_idx)[kMaxTopK],
+                                                     float& lse, float* lds) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const float* pm = p.m + row * nparts;
+  const float* ps = p.s + row * nparts;
+  const float* pv = p.val + row * (int64_t)nparts * k;
+  const int32_t* pi = p.idx + row * (int64_t)nparts * k;
+
+  float tv[K];
+  int32_t ti[K];
+  float run_m = SPEC_NEG_INF, run_s = 0.f;
+  {
+    const bool ok = tid < nparts;
+    const int pc = ok ? tid : nparts - 1;
+    const float m_ = pm[pc], s_ = ps[pc];
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      const int jc = j < k ? j : k - 1;
+      const float v_ = pv[(int64_t)pc * k + jc];
+      const int32_t i_ = pi[(int64_t)pc * k + jc];
+      const bool okj = ok && j < k;
+      tv[j] = okj ? v_ : SPEC_NEG_INF;
+      ti[j] = okj ? i_ : kIdxNone;
+    }
+    if (ok) { run_m = m_; run_s = s_; }
+  }
+  for (int part = tid + 256; part < nparts; part += 256) {   // more parts than threads: fold the rest in
+    const float m_ = pm[part], s_ = ps[part];
+    if (m_ > SPEC_NEG_INF) {
+      const float mn = fmaxf(run_m, m_);
+      run_s = run_s * expf(run_m - mn) + s_ * expf(m_ - mn);
+      run_m = mn;
+    }
+    for (int j = 0; j < k; ++j) {
+      const float v_ = pv[(int64_t)part * k + j];
+      const int32_t i_ = pi[(int64_t)part * k + j];
+      if (before(v_, i_, tv[K - 1], ti[K - 1])) list_insert<K>(tv, ti, v_, i_);
+    }
+  }
+
+  float* red = lds;                                   // [8] block reductions
+  float* xv = lds + 8;                                // [2][4] round exchange, values
+  int32_t* xi = reinterpret_cast<int32_t*>(lds + 16); // [2][4] round exchange, indices
+  const float mx = block_max<256>(run_m, red);
+  const float sum = block_sum<256>(run_m > SPEC_NEG_INF ? run_s * expf(run_m - mx) : 0.f, red);
+  lse = mx + logf(sum);
+
+#pragma unroll
+  for (int j = 0; j < kMaxTopK; ++j) {
+    out_val[j] = SPEC_NEG_INF;
+    out_idx[j] = kIdxNone;
+  }
+#pragma unroll
+  for (int j = 0; j < K; ++j) {
+    if (j < k) {
+      float bv = tv[0];
+      int32_t bi = ti[0];
+      wave_best(bv, bi);
+      const int buf = j & 1;       // double-buffered: one barrier per round
+      if (lane == 0) { xv[buf * 4 + w] = bv; xi[buf * 4 + w] = bi; }
+      __syncthreads();
+      bv = xv[buf * 4];
+      bi = xi[buf * 4];
+#pragma unroll
+      for (int q = 1; q < 4; ++q) {
+        const float ov = xv[buf * 4 + q];
+        const int32_t oi = xi[buf * 4 + q];
+        if (before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+      }
+      if (ti[0] == bi && tv[0] == bv) {  // the owner of the winner pops it
+#pragma unroll
+        for (int q = 0; q + 1 < K; ++q) { tv[q] = tv[q + 1]; ti[q] = ti[q + 1]; }
+        tv[K - 1] = SPEC_NEG_INF;
+        ti[K - 1] = kIdxNone;
+      }
+      out_val[j] = bv;
+      out_idx[j] = bi;
+    }
+  }
+}
+
+__device__ __forceinline__ void block_merge_partials(const Partials& p, int64_t row, int nparts, int k,
+                                                     float (&out_val)[kMaxTopK], int32_t (&out_idx)[kMaxTopK],
+                                                     float& lse, float* lds) {
+  switch (k) {
+    case 1: block_merge_partials_k<1>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
+    case 2: block_merge_partials_k<2>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
+    case 3: block_merge_partials_k<3>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
+    case 4: block_merge_partials_k<4>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
+    case 5:
+    case 6: block_merge_partials_k<6>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
+    default: block_merge_partials_k<8>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
+  }
+}
+
 // k is uniform over the launch: pick the list size that just holds it, so that
 // the common narrow heads (k = 1..3) do not pay for eight slots.
 __device__ __forceinline__ void wave_merge_partials(const Partials& p, int64_t row, int nparts, int k,

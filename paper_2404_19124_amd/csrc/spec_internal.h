@@ -98,6 +98,9 @@ hipError_t launch_row_topk_f32(const float* logits, int64_t ld, int R, int V, in
 // logp[r][v] = logits[r][v] - logsumexp(logits[r])   (in place allowed)
 hipError_t launch_row_log_softmax(const float* logits, float* logp, int64_t ld, int R, int V, hipStream_t st);
 
+// ---- measurement aid: plain copy of n16 16-byte words -----------------------
+hipError_t launch_copy_probe(const void* src, void* dst, int64_t n16, hipStream_t st);
+
 // ---- stage: merge of the previous head's partials + gather + mix + LN + GELU
 struct StageJob {
   int stage;               // 0-based

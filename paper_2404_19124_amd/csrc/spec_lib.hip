@@ -307,6 +307,15 @@ extern "C" spec_status_t spec_profile_read(spec_model_t* m, spec_launch_record_t
   return SPEC_OK;
 }
 
+extern "C" spec_status_t spec_copy_probe(const void* src, void* dst, int64_t bytes, void* hip_stream) {
+  if (!src || !dst) return fail(SPEC_EINVAL, "a required pointer is NULL");
+  if (bytes <= 0 || bytes % 16) return fail(SPEC_EINVAL, "bytes = %lld must be a positive multiple of 16", (long long)bytes);
+  if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15)
+    return fail(SPEC_EINVAL, "src and dst must be 16-byte aligned");
+  HIP_TRY(launch_copy_probe(src, dst, bytes / 16, static_cast<hipStream_t>(hip_stream)));
+  return SPEC_OK;
+}
+
 // One contraction of R state rows against head[stage] (top-k partials, or raw
 // logits into out_head) and, if proj_stage >= 0, against proj[proj_stage]
 // (stored to out_proj).  Returns the number of parts per row it produced.
