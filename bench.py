@@ -220,7 +220,7 @@ def _cpu_baseline(wl, w, state, last, logits, step, budget_s: float):
     O.verify(lg[:1], cand[:1])
     per_seq = time.perf_counter() - t0
     nseq = 1 if per_seq * 2 > budget_s or wl.batch == 1 else nseq
-    reps = max(1, min(5, int(budget_s / max(per_seq * nseq, 1e-3))))
+    reps = max(1, min(60, int(budget_s / max(per_seq * nseq, 1e-3))))
     t0 = time.perf_counter()
     for _ in range(reps):
         d = O.draft(wn, st[:nseq], lt[:nseq], wl.top_k, wl.B, state_dtype=wl.weight_dtype)
