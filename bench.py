@@ -33,7 +33,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
 # labels of spec_launch_record_t.kernel (first template argument of head_gemm_kernel = 16-row
 # fragments per state block)
 KERNEL_NAMES = {0: "head_skinny_kernel", 1: "head_gemm_kernel<2,...>", 2: "head_gemm_kernel<4,...>",
-                3: "head_gemm_kernel<6,...>"}
+                3: "head_gemm_kernel<6,...>", 4: "draft_fused_kernel"}
 
 
 def main() -> int:
@@ -45,6 +45,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--verbose", action="store_true", help="per-shape timing of the contraction launches on stderr")
+    ap.add_argument("--fused", action="store_true",
+                    help="run the draft as one fused launch (spec_set_fused) instead of separate launches")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
                     help="instead of the benchmark: launch the library's plain copy kernel over BYTES a few times "
                          "(calibration of rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -80,6 +82,8 @@ def main() -> int:
     w = W.make_speculator(wl, gen, device="cuda")
     state, last = W.make_draft_inputs(wl, gen, device="cuda")
     step = Step(wl, w)
+    if args.fused:
+        B.spec_set_fused(step.model, True)
     stream = torch.cuda.current_stream()
 
     # inputs of verify: logits boosted at the candidates this draft produces

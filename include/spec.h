@@ -158,7 +158,8 @@ spec_status_t spec_head_logp(spec_model_t* m, int32_t stage, const void* states,
  * roofline reports.  While enabled, spec_draft attaches a pair of HIP events to
  * every contraction launch (they receive that kernel's begin / end time on the
  * caller's stream); nothing else changes.
- *   kernel: 0 = rows<=16 streaming kernel, 1..3 = dense kernel with 32/64/96-row state blocks
+ *   kernel: 0 = rows<=16 streaming kernel, 1..3 = dense kernel with 32/64/96-row state blocks,
+ *           4 = whole draft in one launch (rows / weight_rows summed over its contractions)
  *   rows, weight_rows, k: the contraction is [rows, k] x [weight_rows, k]^T
  *                  (weight_rows counts head and fused next-projection rows together)
  *   ms: elapsed time between the two events */
@@ -174,6 +175,25 @@ spec_status_t spec_profile_enable(spec_model_t* m, int32_t capacity);
 /* Waits for the recorded events, writes up to `cap` records to `out` (host) in launch
  * order, stores their number in *n (host) and clears the recording. */
 spec_status_t spec_profile_read(spec_model_t* m, spec_launch_record_t* out, int32_t cap, int32_t* n);
+
+/* Optional launch mode of spec_draft, OFF by default.  When enabled and every stage of a
+ * call has at most 16 rows (batch 1 with the paper's trees) and the model is SPEC_BF16 with
+ * emb_dim == inner_dim in {512, 1024, 2048, 3072, 4096}, spec_draft runs the whole draft
+ * (Sec. 3.1, 4.1) as ONE kernel launch whose phases are separated by a device-wide
+ * barrier instead of a sequence of launches.  Both modes give bit-identical results; on
+ * MI355X the sequence of launches is the faster one (a kernel boundary costs less than
+ * the barrier), which is why it is the default.  The fused launch needs all its
+ * workgroups resident at once (one per compute unit); should that not hold, its barrier
+ * gives up after about 2 s, the NEXT spec_draft on the model returns SPEC_EHIP (the
+ * candidates of the failed call are invalid) and the mode switches itself off. */
+spec_status_t spec_set_fused(spec_model_t* m, int32_t enable);
+
+/* Durations, in microseconds, between the phase boundaries of the model's last fused
+ * draft launch as seen by its first workgroup: [proj_1][barrier][stage_1 + barrier + head_1]
+ * [barrier][stage_2 + barrier + head_2] ... [barrier][tree].  Synchronises with the device
+ * (call after the stream is idle).  us: host array of `cap` floats; *n (host) receives the
+ * number written (0 when no fused launch has run). */
+spec_status_t spec_fused_phase_us(spec_model_t* m, float* us, int32_t cap, int32_t* n);
 
 /* Measurement aid, not a step of the method: one launch of a plain copy kernel that
  * reads `bytes` from src (dev) and writes them to dst (dev; must not overlap src).  Its HBM

@@ -25,6 +25,7 @@ SOURCES = [
     "kernels_f32.hip",
     "kernels_head_skinny.hip",
     "kernels_head_gemm.hip",
+    "kernels_draft_fused.hip",
 ]
 
 FLAGS = [

@@ -5,6 +5,32 @@
 
 namespace specdraft {
 
+// Stores of results that OTHER workgroups of the same launch read after a device-wide
+// barrier (the whole-draft kernel): agent-scope stores are written through to memory,
+// past the writer's own XCD-local L2, so that a reader on another XCD finds them without
+// any cache having to be written back as a whole.  In the stand-alone kernels they cost
+// nothing extra (the data is a few KB).
+__device__ __forceinline__ void store_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_agent(int32_t* p, int32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_agent(uint64_t* p, uint64_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// threadIdx.x as a value the optimiser cannot look through.  The phase bodies that the
+// fused whole-draft kernel runs in a loop derive every per-thread index from it, so
+// that the compiler does not hoist those computations out of the loop and keep dozens
+// of registers alive across all phases.
+__device__ __forceinline__ int opaque_tid() {
+  int t = threadIdx.x;
+  asm volatile("" : "+v"(t));
+  return t;
+}
+
+
 #define SPEC_NEG_INF (-__builtin_huge_valf())
 constexpr int32_t kIdxNone = 0x7fffffff;
 

@@ -3,145 +3,15 @@
 // The token a node carries is the j-th best of its parent's head row; that row's
 // partial results are merged here (every sibling repeats the small merge, which
 // saves a separate launch on the latency-critical batch-1 chain).
-#include "merge.h"
-#include "spec_internal.h"
+#include "stage_body.h"
 
 namespace specdraft {
 
 // NCH = 8-element chunks per thread held in registers (D <= NCH * 2048).
 template <bool BF16, int NCH>
 __global__ __launch_bounds__(256) void stage_kernel(StageJob j) {
-  __shared__ float scratch[8];
-  __shared__ float merge_lds[32];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int r = blockIdx.x;
-  const int parent = r / j.k_prev, rank = r - parent * j.k_prev;
-  const int D = j.D, nchunk = D / 8;
-
-  // everything that does not depend on the token is requested first: the
-  // projected parent state and the LayerNorm affine
-  const float* pz = j.pz + (int64_t)parent * D;
-  float z[NCH][8], ga[NCH][8], be[NCH][8];
-#pragma unroll
-  for (int ci = 0; ci < NCH; ++ci) {
-    const int c = tid + ci * 256;
-    if (c < nchunk) {
-      const float4 p0 = *reinterpret_cast<const float4*>(pz + c * 8);
-      const float4 p1 = *reinterpret_cast<const float4*>(pz + c * 8 + 4);
-      const float4 g0 = *reinterpret_cast<const float4*>(j.gamma + c * 8);
-      const float4 g1 = *reinterpret_cast<const float4*>(j.gamma + c * 8 + 4);
-      const float4 b0 = *reinterpret_cast<const float4*>(j.beta + c * 8);
-      const float4 b1 = *reinterpret_cast<const float4*>(j.beta + c * 8 + 4);
-      z[ci][0] = p0.x; z[ci][1] = p0.y; z[ci][2] = p0.z; z[ci][3] = p0.w;
-      z[ci][4] = p1.x; z[ci][5] = p1.y; z[ci][6] = p1.z; z[ci][7] = p1.w;
-      ga[ci][0] = g0.x; ga[ci][1] = g0.y; ga[ci][2] = g0.z; ga[ci][3] = g0.w;
-      ga[ci][4] = g1.x; ga[ci][5] = g1.y; ga[ci][6] = g1.z; ga[ci][7] = g1.w;
-      be[ci][0] = b0.x; be[ci][1] = b0.y; be[ci][2] = b0.z; be[ci][3] = b0.w;
-      be[ci][4] = b1.x; be[ci][5] = b1.y; be[ci][6] = b1.z; be[ci][7] = b1.w;
-    }
-  }
-
-  int tok;
-  if (j.stage == 0) {
-    tok = j.last_tok[r];
-  } else {
-    float v[kMaxTopK];
-    int32_t ix[kMaxTopK];
-    float lse;
-    block_merge_partials(j.part, parent, j.nparts, j.k_prev, v, ix, lse, merge_lds);
-    tok = ix[0];
-#pragma unroll
-    for (int q = 1; q < kMaxTopK; ++q)
-      if (q == rank) tok = ix[q];
-    if (rank == 0 && tid < 64) {
-#pragma unroll
-      for (int q = 0; q < kMaxTopK; ++q)
-        if (lane == q && q < j.k_prev) {
-          j.prev_tok[(int64_t)parent * j.k_prev + q] = ix[q];
-          j.prev_logp[(int64_t)parent * j.k_prev + q] = v[q] - lse;
-        }
-      if (lane == 0) j.prev_lse[parent] = lse;
-    }
-  }
-  tok = min(max(tok, 0), j.V - 1);  // a wild token from the caller must not leave the table
-
-  // gather + mix
-  float lsum = 0.f;
-#pragma unroll
-  for (int ci = 0; ci < NCH; ++ci) {
-    const int c = tid + ci * 256;
-    if (c < nchunk) {
-      float e[8];
-      if (BF16) {
-        const uint4 raw =
-            *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(j.emb) + (int64_t)tok * D + c * 8);
-        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          e[2 * q] = bf16_bits_to_f32(w[q] & 0xffffu);
-          e[2 * q + 1] = bf16_bits_to_f32(w[q] >> 16);
-        }
-      } else {
-        const float* er = static_cast<const float*>(j.emb) + (int64_t)tok * D + c * 8;
-        const float4 e0 = *reinterpret_cast<const float4*>(er);
-        const float4 e1 = *reinterpret_cast<const float4*>(er + 4);
-        e[0] = e0.x; e[1] = e0.y; e[2] = e0.z; e[3] = e0.w;
-        e[4] = e1.x; e[5] = e1.y; e[6] = e1.z; e[7] = e1.w;
-      }
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        z[ci][q] = j.w_s * z[ci][q] + j.w_e * e[q];
-        lsum += z[ci][q];
-      }
-    }
-  }
-  const float mean = block_sum<256>(lsum, scratch) / (float)D;
-  float lvar = 0.f;
-#pragma unroll
-  for (int ci = 0; ci < NCH; ++ci) {
-    if (tid + ci * 256 < nchunk) {
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        const float d = z[ci][q] - mean;
-        lvar += d * d;
-      }
-    }
-  }
-  const float var = block_sum<256>(lvar, scratch) / (float)D;
-  const float rstd = 1.0f / sqrtf(var + j.eps);
-
-#pragma unroll
-  for (int ci = 0; ci < NCH; ++ci) {
-    const int c = tid + ci * 256;
-    if (c < nchunk) {
-      float s[8];
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        const float y = (z[ci][q] - mean) * rstd * ga[ci][q] + be[ci][q];
-        s[q] = 0.5f * y * (1.0f + erff(y * 0.70710678118654752440f));
-      }
-      if (BF16) {
-        uint4 o;
-        o.x = f32_to_bf16_bits(s[0]) | (f32_to_bf16_bits(s[1]) << 16);
-        o.y = f32_to_bf16_bits(s[2]) | (f32_to_bf16_bits(s[3]) << 16);
-        o.z = f32_to_bf16_bits(s[4]) | (f32_to_bf16_bits(s[5]) << 16);
-        o.w = f32_to_bf16_bits(s[6]) | (f32_to_bf16_bits(s[7]) << 16);
-        // tiled layout: row tile r/16, column fragment c/4, lane slot (c%4)*16 + r%16
-        const int64_t slot = ((int64_t)(r >> 4) * (D / 32) + (c >> 2)) * 64 + ((c & 3) << 4) + (r & 15);
-        reinterpret_cast<uint4*>(j.state_out)[slot] = o;
-        if (j.state_dbg) reinterpret_cast<uint4*>(j.state_dbg)[((int64_t)r * D) / 8 + c] = o;
-      } else {
-        float* so = static_cast<float*>(j.state_out) + (int64_t)r * D + c * 8;
-        *reinterpret_cast<float4*>(so) = make_float4(s[0], s[1], s[2], s[3]);
-        *reinterpret_cast<float4*>(so + 4) = make_float4(s[4], s[5], s[6], s[7]);
-        if (j.state_dbg) {
-          float* sd = static_cast<float*>(j.state_dbg) + (int64_t)r * D + c * 8;
-          *reinterpret_cast<float4*>(sd) = make_float4(s[0], s[1], s[2], s[3]);
-          *reinterpret_cast<float4*>(sd + 4) = make_float4(s[4], s[5], s[6], s[7]);
-        }
-      }
-    }
-  }
+  __shared__ float lds[64];
+  stage_row<BF16, NCH, 256>(j, blockIdx.x, lds);
 }
 
 template <bool BF16>
@@ -168,76 +38,21 @@ hipError_t launch_stage(const StageJob& job, hipStream_t st) {
 // widest merge needs more than the 128 a 1024-thread workgroup would leave it).
 __global__ __launch_bounds__(512) void tree_kernel(TreeJob j) {
   __shared__ float sc[kMaxLeaves];
-  // per-stage tables of the job in LDS: indexing kernel arguments with a run-time
-  // stage number would make the compiler spill the whole argument block to scratch
   __shared__ int s_k[kMaxStages];
   __shared__ int64_t s_off[kMaxStages];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int q = blockIdx.x;
-  const int n = j.n, L = j.L;
-  int k_last = 1;
-  int64_t off_last = 0, row_off_last = 0;
+  __shared__ float merge_lds[64];
+  TreeArgs a;
+  a.n = j.n; a.B = j.B; a.L = j.L; a.nparts = j.nparts;
+  a.k_last = 1; a.off_last = 0; a.row_off_last = 0;
 #pragma unroll
   for (int i = 0; i < kMaxStages; ++i) {
-    if (tid == i) { s_k[i] = j.top_k[i]; s_off[i] = j.off[i]; }
-    if (i == n - 1) { k_last = j.top_k[i]; off_last = j.off[i]; row_off_last = j.row_off[i]; }
+    if ((int)threadIdx.x == i) { s_k[i] = j.top_k[i]; s_off[i] = j.off[i]; }
+    if (i == j.n - 1) { a.k_last = j.top_k[i]; a.off_last = j.off[i]; a.row_off_last = j.row_off[i]; }
   }
-  const int rows_last = L / k_last;
-
-  for (int rl = wave; rl < rows_last; rl += 8) {
-    const int64_t row = (int64_t)q * rows_last + rl;
-    float v[kMaxTopK];
-    int32_t ix[kMaxTopK];
-    float lse;
-    wave_merge_partials(j.part, row, j.nparts, k_last, v, ix, lse);
-#pragma unroll
-    for (int t = 0; t < kMaxTopK; ++t)
-      if (lane == t && t < k_last) {
-        j.tok[off_last + row * k_last + t] = ix[t];
-        j.logp[off_last + row * k_last + t] = v[t] - lse;
-      }
-    if (lane == 0) j.lse[row_off_last + row] = lse;
-  }
-  __threadfence_block();
+  a.part = j.part; a.tok = j.tok; a.logp = j.logp; a.lse = j.lse;
+  a.cand_tokens = j.cand_tokens; a.cand_scores = j.cand_scores; a.cand_leaf = j.cand_leaf;
   __syncthreads();
-
-  for (int leaf = tid; leaf < L; leaf += 512) {
-    float score = 0.f;
-    int64_t row = q;
-    int stride = L;
-    for (int i = 0; i < n; ++i) {
-      const int k = s_k[i];
-      stride /= k;
-      const int rank = (leaf / stride) % k;
-      score += j.logp[s_off[i] + row * k + rank];
-      row = row * k + rank;
-    }
-    sc[leaf] = score;
-  }
-  __syncthreads();
-
-  for (int leaf = tid; leaf < L; leaf += 512) {
-    const float s = sc[leaf];
-    int pos = 0;
-    for (int o = 0; o < L; ++o) {
-      const float so = sc[o];
-      pos += ((so > s) || (so == s && o < leaf)) ? 1 : 0;
-    }
-    if (pos < j.B) {
-      const int64_t c = (int64_t)q * j.B + pos;
-      j.cand_leaf[c] = leaf;
-      j.cand_scores[c] = s;
-      int64_t row = q;
-      int stride = L;
-      for (int i = 0; i < n; ++i) {
-        const int k = s_k[i];
-        stride /= k;
-        const int rank = (leaf / stride) % k;
-        j.cand_tokens[c * n + i] = j.tok[s_off[i] + row * k + rank];
-        row = row * k + rank;
-      }
-    }
-  }
+  tree_body<512, kMaxTopK>(a, blockIdx.x, s_k, s_off, sc, merge_lds);
 }
 
 hipError_t launch_tree(const TreeJob& job, hipStream_t st) {

@@ -37,7 +37,7 @@ template <int K>
 __device__ __forceinline__ void wave_merge_partials_k(const Partials& p, int64_t row, int nparts, int k,
                                                     float (&out_val)[kMaxTopK], int32_t (&out_idx)[kMaxTopK],
                                                     float& lse) {
-  const int lane = threadIdx.x & 63;
+  const int lane = opaque_tid() & 63;
   const float* pm = p.m + row * nparts;
   const float* ps = p.s + row * nparts;
   const float* pv = p.val + row * (int64_t)nparts * k;
@@ -114,16 +114,19 @@ __device__ __forceinline__ void wave_merge_partials_k(const Partials& p, int64_t
   }
 }
 
-// The same merge done by a whole 256-thread workgroup for ONE row: with at most 256
-// parts every thread holds exactly one part's (already sorted) list, so nothing has to
-// be inserted; the k results are popped with one wave reduction plus a 4-entry
-// exchange through LDS per round.  All 256 threads must call; every thread receives
-// the result.  `lds` needs 32 words.
+// The same merge done by a group of 256 consecutive threads for ONE row: with at most
+// 256 parts every thread holds exactly one part's (already sorted) list, so nothing has
+// to be inserted; the k results are popped with one wave reduction plus a 4-entry
+// exchange through LDS per round.  A workgroup of 256 * n threads runs n such groups
+// side by side (each on its own row, or all on the same one): the function contains
+// workgroup barriers, so EVERY thread of the workgroup must call it, with the same k
+// and nparts; every thread receives its group's result.  `lds` is the group's own
+// scratch of 32 words.
 template <int K>
-__device__ __forceinline__ void block_merge_partials_k(const Partials& p, int64_t row, int nparts, int k,
+__device__ __forceinline__ void group_merge_partials_k(const Partials& p, int64_t row, int nparts, int k,
                                                      float (&out_val)[kMaxTopK], int32_t (&out_idx)[kMaxTopK],
                                                      float& lse, float* lds) {
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int gt = opaque_tid() & 255, lane = gt & 63, w = gt >> 6;
   const float* pm = p.m + row * nparts;
   const float* ps = p.s + row * nparts;
   const float* pv = p.val + row * (int64_t)nparts * k;
@@ -133,8 +136,8 @@ __device__ __forceinline__ void block_merge_partials_k(const Partials& p, int64_
   int32_t ti[K];
   float run_m = SPEC_NEG_INF, run_s = 0.f;
   {
-    const bool ok = tid < nparts;
-    const int pc = ok ? tid : nparts - 1;
+    const bool ok = gt < nparts;
+    const int pc = ok ? gt : nparts - 1;
     const float m_ = pm[pc], s_ = ps[pc];
 #pragma unroll
     for (int j = 0; j < K; ++j) {
@@ -147,7 +150,7 @@ __device__ __forceinline__ void block_merge_partials_k(const Partials& p, int64_
     }
     if (ok) { run_m = m_; run_s = s_; }
   }
-  for (int part = tid + 256; part < nparts; part += 256) {   // more parts than threads: fold the rest in
+  for (int part = gt + 256; part < nparts; part += 256) {   // more parts than threads: fold the rest in
     const float m_ = pm[part], s_ = ps[part];
     if (m_ > SPEC_NEG_INF) {
       const float mn = fmaxf(run_m, m_);
@@ -161,12 +164,18 @@ __device__ __forceinline__ void block_merge_partials_k(const Partials& p, int64_
     }
   }
 
-  float* red = lds;                                   // [8] block reductions
+  float* red = lds;                                   // [2][4] reductions of the group's four waves
   float* xv = lds + 8;                                // [2][4] round exchange, values
   int32_t* xi = reinterpret_cast<int32_t*>(lds + 16); // [2][4] round exchange, indices
-  const float mx = block_max<256>(run_m, red);
-  const float sum = block_sum<256>(run_m > SPEC_NEG_INF ? run_s * expf(run_m - mx) : 0.f, red);
-  lse = mx + logf(sum);
+  const float wm = wave_max(run_m);
+  __syncthreads();                                    // scratch may still be read from an earlier call
+  if (lane == 0) red[w] = wm;
+  __syncthreads();
+  const float mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  const float wsum = wave_sum(run_m > SPEC_NEG_INF ? run_s * expf(run_m - mx) : 0.f);
+  if (lane == 0) red[4 + w] = wsum;
+  __syncthreads();
+  lse = mx + logf((red[4] + red[5]) + (red[6] + red[7]));
 
 #pragma unroll
   for (int j = 0; j < kMaxTopK; ++j) {
@@ -202,17 +211,17 @@ __device__ __forceinline__ void block_merge_partials_k(const Partials& p, int64_
   }
 }
 
-__device__ __forceinline__ void block_merge_partials(const Partials& p, int64_t row, int nparts, int k,
+__device__ __forceinline__ void group_merge_partials(const Partials& p, int64_t row, int nparts, int k,
                                                      float (&out_val)[kMaxTopK], int32_t (&out_idx)[kMaxTopK],
                                                      float& lse, float* lds) {
   switch (k) {
-    case 1: block_merge_partials_k<1>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
-    case 2: block_merge_partials_k<2>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
-    case 3: block_merge_partials_k<3>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
-    case 4: block_merge_partials_k<4>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
+    case 1: group_merge_partials_k<1>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
+    case 2: group_merge_partials_k<2>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
+    case 3: group_merge_partials_k<3>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
+    case 4: group_merge_partials_k<4>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
     case 5:
-    case 6: block_merge_partials_k<6>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
-    default: block_merge_partials_k<8>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
+    case 6: group_merge_partials_k<6>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
+    default: group_merge_partials_k<8>(p, row, nparts, k, out_val, out_idx, lse, lds); break;
   }
 }
 

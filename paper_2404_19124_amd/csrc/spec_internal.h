@@ -143,6 +143,24 @@ struct TreeJob {
 };
 hipError_t launch_tree(const TreeJob& job, hipStream_t st);
 
+// ---- whole draft in one launch (every stage <= 16 rows) ---------------------
+struct FusedJob {
+  int n, batch, n_wg;
+  unsigned barrier_base;             // barriers completed on `barrier` before this launch (wraps)
+  unsigned* barrier;                 // words of the device-wide barrier (fused_barrier_bytes(), zeroed once)
+  int* fail_flag;                    // host-visible: set to 1 when a barrier wait ran out of time
+  unsigned long long* clocks;        // optional: 2n + 4 wall-clock stamps (100 MHz) of workgroup 0
+  unsigned long long timeout_ticks;  // bound of one barrier wait, wall-clock ticks
+  HeadJob head[kMaxStages + 1];      // [0] = proj_1 alone, [i + 1] = head_i (+ proj_{i+1})
+  StageJob stage[kMaxStages];
+  TreeJob tree;
+};
+constexpr int kFusedBarriers(int n) { return 2 * n + 1; }
+bool fused_fits(int max_rows, int kt_in, int kt, int n_cu);
+size_t fused_barrier_bytes();
+hipError_t launch_draft_fused(const FusedJob& job, int max_rows, hipStream_t st, hipEvent_t ev_start = nullptr,
+                              hipEvent_t ev_stop = nullptr);
+
 // ---- verify ----------------------------------------------------------------
 hipError_t launch_argmax_rows(const void* logits, int bf16, int64_t rows, int V, int32_t* greedy, hipStream_t st);
 hipError_t launch_accept(const int32_t* greedy, const int32_t* cand, int batch, int B, int n, int32_t* accept_len,

@@ -71,6 +71,22 @@ struct spec_model {
   std::vector<hipEvent_t> ev;   // 2 per record slot
   std::vector<Rec> rec;
   int prof_cap = 0, prof_n = 0;
+  // whole-draft kernel: words of its device-wide barrier (monotone: the host counts the
+  // barriers completed so far), failure flag in host-visible memory,
+  // phase time stamps of the last launch
+  unsigned* barrier = nullptr;
+  unsigned barrier_value = 0;
+  int* fail_host = nullptr;
+  int* fail_dev = nullptr;
+  unsigned long long* clocks = nullptr;
+  int clocks_n = 0;
+  bool fused_enabled = false;  // opt-in (spec_set_fused): measured slower than separate launches
+  // Workspace of the whole-draft kernel, one set PER STAGE: inside one launch a buffer
+  // that other workgroups read is written once and never read before that, so no cache
+  // can hold a stale line of it (see kernels_draft_fused.hip)
+  void* fstates[kMaxStages] = {};
+  float* fpz[kMaxStages] = {};
+  Partials fpart[kMaxStages] = {};
 };
 
 static void free_model(spec_model* m) {
@@ -78,6 +94,7 @@ static void free_model(spec_model* m) {
   for (hipEvent_t e : m->ev) (void)hipEventDestroy(e);
   for (void* p : m->owned)
     if (p) (void)hipFree(p);
+  if (m->fail_host) (void)hipHostFree(m->fail_host);
   delete m;
 }
 
@@ -241,6 +258,24 @@ extern "C" spec_status_t spec_create(const spec_config_t* cfg, const spec_weight
   m->logits_rows = m->bf16 ? 0 : max_rows;
   TRY_FREE(dev_alloc(m, &m->logits, (size_t)m->logits_rows * V * 4));
 
+  if (m->bf16) {
+    const size_t slots = (size_t)16 * skinny_grid(m->n_cu);
+    for (int i = 0; i < n; ++i) {
+      TRY_FREE(dev_alloc(m, &m->fstates[i], (size_t)16 * D * 2));
+      TRY_FREE(dev_alloc(m, &m->fpz[i], (size_t)16 * D * 4));
+      TRY_FREE(dev_alloc(m, &m->fpart[i].m, slots * 4));
+      TRY_FREE(dev_alloc(m, &m->fpart[i].s, slots * 4));
+      TRY_FREE(dev_alloc(m, &m->fpart[i].val, slots * kMaxTopK * 4));
+      TRY_FREE(dev_alloc(m, &m->fpart[i].idx, slots * kMaxTopK * 4));
+    }
+  }
+  TRY_FREE(dev_alloc(m, &m->barrier, fused_barrier_bytes()));
+  HIP_TRY_FREE(hipMemsetAsync(m->barrier, 0, fused_barrier_bytes(), stream));
+  TRY_FREE(dev_alloc(m, &m->clocks, (2 * kMaxStages + 4) * sizeof(unsigned long long)));
+  HIP_TRY_FREE(hipHostMalloc(reinterpret_cast<void**>(&m->fail_host), 64, hipHostMallocMapped));
+  *m->fail_host = 0;
+  HIP_TRY_FREE(hipHostGetDevicePointer(reinterpret_cast<void**>(&m->fail_dev), m->fail_host, 0));
+
   HIP_TRY_FREE(hipStreamSynchronize(stream));
 #undef TRY_FREE
 #undef HIP_TRY_FREE
@@ -316,17 +351,34 @@ extern "C" spec_status_t spec_copy_probe(const void* src, void* dst, int64_t byt
   return SPEC_OK;
 }
 
+extern "C" spec_status_t spec_set_fused(spec_model_t* m, int32_t enable) {
+  if (!m) return fail(SPEC_EINVAL, "model is NULL");
+  m->fused_enabled = enable != 0;
+  return SPEC_OK;
+}
+
+extern "C" spec_status_t spec_fused_phase_us(spec_model_t* m, float* us, int32_t cap, int32_t* n) {
+  if (!m || !us || !n) return fail(SPEC_EINVAL, "a required pointer is NULL");
+  unsigned long long t[2 * kMaxStages + 4] = {0};
+  const int cnt = m->clocks_n;
+  *n = 0;
+  if (cnt < 2) return SPEC_OK;
+  HIP_TRY(hipMemcpy(t, m->clocks, (size_t)cnt * sizeof(t[0]), hipMemcpyDeviceToHost));
+  int w = 0;
+  for (int i = 0; i + 1 < cnt && w < cap; ++i) us[w++] = (float)((double)(t[i + 1] - t[i]) * 0.01);  // 100 MHz
+  *n = w;
+  return SPEC_OK;
+}
+
 // One contraction of R state rows against head[stage] (top-k partials, or raw
 // logits into out_head) and, if proj_stage >= 0, against proj[proj_stage]
 // (stored to out_proj).  Returns the number of parts per row it produced.
-static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, const void* b_src, bool b_rowmajor,
-                                     int b_ld, int R, int k_top, float* out_head, float* out_proj, int* nparts,
-                                     hipStream_t st) {
+static HeadJob make_head_job(const spec_model* m, int stage, int proj_stage, const void* b_src, bool b_rowmajor,
+                             int b_ld, int R, int k_top, float* out_head, float* out_proj) {
   const int D = m->cfg.inner_dim, V = m->cfg.vocab;
   HeadJob job;
   memset(&job, 0, sizeof(job));
-  const int K = b_ld;
-  job.kt = K / 32;
+  job.kt = b_ld / 32;
   job.b_src = b_src;
   job.b_rowmajor = b_rowmajor ? 1 : 0;
   job.b_ld = b_ld;
@@ -347,6 +399,14 @@ static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, c
     job.vt_proj = (D + 15) / 16;
     job.n_proj = D;
   }
+  return job;
+}
+
+static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, const void* b_src, bool b_rowmajor,
+                                     int b_ld, int R, int k_top, float* out_head, float* out_proj, int* nparts,
+                                     hipStream_t st) {
+  HeadJob job = make_head_job(m, stage, proj_stage, b_src, b_rowmajor, b_ld, R, k_top, out_head, out_proj);
+  const int K = b_ld;
   if (skinny_fits(R, job.kt)) {
     job.nparts = skinny_grid(m->n_cu);
     *nparts = job.nparts;
@@ -403,17 +463,16 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
     }
   }
 
-  int nparts = 1;
-  // projection of the base model's state for stage 1
-  if (m->bf16) {
-    spec_status_t s = run_contraction(m, -1, 0, state, true, E, batch, 0, nullptr, m->pz[0], &nparts, st);
-    if (s != SPEC_OK) return s;
-  } else {
-    HIP_TRY(launch_gemm_f32(static_cast<const float*>(state), E, static_cast<const float*>(m->proj[0]), E, m->pz[0], D,
-                            batch, D, E, st));
+  if (*m->fail_host) {
+    // an earlier whole-draft launch gave up at its device-wide barrier: its results were
+    // invalid, and the arrival counter is in an unknown state
+    *m->fail_host = 0;
+    m->fused_enabled = false;
+    return fail(SPEC_EHIP, "an earlier fused draft launch timed out at its device-wide barrier (workgroups not "
+                           "co-resident); its results are invalid; further drafts use separate launches");
   }
 
-  for (int i = 0; i < n; ++i) {
+  auto stage_job = [&](int i, int nparts) {
     StageJob sj;
     memset(&sj, 0, sizeof(sj));
     sj.stage = i;
@@ -441,44 +500,97 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
     sj.state_dbg = (dbg && dbg->stage_state)
                        ? static_cast<void*>(static_cast<char*>(dbg->stage_state) + (size_t)row_off[i] * D * m->esz)
                        : nullptr;
-    HIP_TRY(launch_stage(sj, st));
+    return sj;
+  };
+  auto tree_job = [&](int nparts) {
+    TreeJob tj;
+    memset(&tj, 0, sizeof(tj));
+    tj.batch = batch;
+    tj.n = n;
+    tj.B = B;
+    tj.L = (int)L;
+    for (int i = 0; i < n; ++i) {
+      tj.top_k[i] = top_k[i];
+      tj.off[i] = off[i];
+      tj.row_off[i] = row_off[i];
+    }
+    for (int i = n; i < kMaxStages; ++i) tj.top_k[i] = 1;
+    tj.part = m->part;
+    tj.nparts = nparts;
+    tj.tok = m->tok;
+    tj.logp = m->logp;
+    tj.lse = m->lse;
+    tj.cand_tokens = cand_tokens;
+    tj.cand_scores = cand_scores;
+    tj.cand_leaf = cand_leaf;
+    return tj;
+  };
 
-    const int proj_next = i + 1 < n ? i + 1 : -1;
+  // every stage at most 16 rows (batch 1 with the paper's trees): the whole draft in one launch
+  const int grid = skinny_grid(m->n_cu);
+  bool fused = m->bf16 && m->fused_enabled && R[n - 1] <= 16 && batch <= 16 &&
+               fused_fits((int)R[n - 1] > batch ? (int)R[n - 1] : batch, E / 32, D / 32, grid);
+  if (fused) {
+    FusedJob fj;
+    memset(&fj, 0, sizeof(fj));
+    fj.n = n;
+    fj.batch = batch;
+    fj.n_wg = grid;
+    fj.barrier_base = m->barrier_value;
+    fj.barrier = m->barrier;
+    fj.fail_flag = m->fail_dev;
+    fj.clocks = m->clocks;
+    fj.timeout_ticks = 200000000ull;  // 2 s of the 100 MHz wall clock
+    fj.head[0] = make_head_job(m, -1, 0, state, true, E, batch, 0, nullptr, m->fpz[0]);
+    fj.head[0].nparts = grid;
+    int64_t sum_rows = batch;
+    for (int i = 0; i < n; ++i) {
+      fj.stage[i] = stage_job(i, grid);
+      fj.stage[i].pz = m->fpz[i];
+      fj.stage[i].state_out = m->fstates[i];
+      if (i > 0) fj.stage[i].part = m->fpart[i - 1];
+      fj.head[i + 1] = make_head_job(m, i, i + 1 < n ? i + 1 : -1, m->fstates[i], false, D, (int)R[i], top_k[i],
+                                     nullptr, i + 1 < n ? m->fpz[i + 1] : nullptr);
+      fj.head[i + 1].part = m->fpart[i];
+      fj.head[i + 1].nparts = grid;
+      sum_rows += R[i];
+    }
+    fj.tree = tree_job(grid);
+    fj.tree.part = m->fpart[n - 1];
+    const int slot = prof_slot(m, 4, (int)sum_rows, n * V + n * D, D);
+    HIP_TRY(launch_draft_fused(fj, (int)R[n - 1] > batch ? (int)R[n - 1] : batch, st, EV0(slot), EV1(slot)));
+    m->barrier_value += (unsigned)kFusedBarriers(n);
+    m->clocks_n = 2 * n + 4;
+  } else {
+    int nparts = 1;
+    // projection of the base model's state for stage 1
     if (m->bf16) {
-      spec_status_t s = run_contraction(m, i, proj_next, m->states, false, D, (int)R[i], top_k[i], nullptr,
-                                        m->pz[(i + 1) & 1], &nparts, st);
+      spec_status_t s = run_contraction(m, -1, 0, state, true, E, batch, 0, nullptr, m->pz[0], &nparts, st);
       if (s != SPEC_OK) return s;
     } else {
-      const float* sf = static_cast<const float*>(m->states);
-      HIP_TRY(launch_gemm_f32(sf, D, static_cast<const float*>(m->head[i]), D, m->logits, V, (int)R[i], V, D, st));
-      HIP_TRY(launch_row_topk_f32(m->logits, V, (int)R[i], V, top_k[i], m->part, st));
-      nparts = 1;
-      if (proj_next >= 0)
-        HIP_TRY(launch_gemm_f32(sf, D, static_cast<const float*>(m->proj[proj_next]), D, m->pz[(i + 1) & 1], D,
-                                (int)R[i], D, D, st));
+      HIP_TRY(launch_gemm_f32(static_cast<const float*>(state), E, static_cast<const float*>(m->proj[0]), E, m->pz[0],
+                              D, batch, D, E, st));
     }
-  }
 
-  TreeJob tj;
-  memset(&tj, 0, sizeof(tj));
-  tj.batch = batch;
-  tj.n = n;
-  tj.B = B;
-  tj.L = (int)L;
-  for (int i = 0; i < n; ++i) {
-    tj.top_k[i] = top_k[i];
-    tj.off[i] = off[i];
-    tj.row_off[i] = row_off[i];
+    for (int i = 0; i < n; ++i) {
+      HIP_TRY(launch_stage(stage_job(i, nparts), st));
+      const int proj_next = i + 1 < n ? i + 1 : -1;
+      if (m->bf16) {
+        spec_status_t s = run_contraction(m, i, proj_next, m->states, false, D, (int)R[i], top_k[i], nullptr,
+                                          m->pz[(i + 1) & 1], &nparts, st);
+        if (s != SPEC_OK) return s;
+      } else {
+        const float* sf = static_cast<const float*>(m->states);
+        HIP_TRY(launch_gemm_f32(sf, D, static_cast<const float*>(m->head[i]), D, m->logits, V, (int)R[i], V, D, st));
+        HIP_TRY(launch_row_topk_f32(m->logits, V, (int)R[i], V, top_k[i], m->part, st));
+        nparts = 1;
+        if (proj_next >= 0)
+          HIP_TRY(launch_gemm_f32(sf, D, static_cast<const float*>(m->proj[proj_next]), D, m->pz[(i + 1) & 1], D,
+                                  (int)R[i], D, D, st));
+      }
+    }
+    HIP_TRY(launch_tree(tree_job(nparts), st));
   }
-  tj.part = m->part;
-  tj.nparts = nparts;
-  tj.tok = m->tok;
-  tj.logp = m->logp;
-  tj.lse = m->lse;
-  tj.cand_tokens = cand_tokens;
-  tj.cand_scores = cand_scores;
-  tj.cand_leaf = cand_leaf;
-  HIP_TRY(launch_tree(tj, st));
 
   if (dbg) {
     const int64_t nk = off[n - 1] + R[n - 1] * top_k[n - 1], nr = row_off[n - 1] + R[n - 1];

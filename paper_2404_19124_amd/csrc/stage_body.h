@@ -1,0 +1,267 @@
+// Device-side bodies of the stage step and of the tree step (Sec. 3.1, 4.1 of the
+// paper), shared by the stand-alone kernels and the fused whole-draft kernel.
+#pragma once
+#include "merge.h"
+#include "spec_internal.h"
+
+namespace specdraft {
+
+// One node (child row r) of a stage, computed by a whole workgroup of NT threads:
+//   state = GELU(LayerNorm(w_s * (W s_parent) + w_e * Emb[token]))
+// The token the node carries is the rank-th best of its parent's head row; that row's
+// partial results are merged here (every sibling repeats the small merge, which saves
+// a separate launch on the latency-critical batch-1 chain).
+// NCH = 8-element chunks per thread held in registers (D <= NCH * NT * 8).
+// `lds`: (NT / 256) * 32 + 32 words of scratch.  Contains workgroup barriers.
+template <bool BF16, int NCH, int NT>
+__device__ __forceinline__ void stage_row(const StageJob& j, int r, float* lds) {
+  float* scratch = lds;                 // NT / 64 <= 16 words
+  const int tid = opaque_tid(), lane = tid & 63;
+  float* merge_lds = lds + 32 + (tid >> 8) * 32;
+  const int parent = r / j.k_prev, rank = r - parent * j.k_prev;
+  const int D = j.D, nchunk = D / 8;
+
+  // everything that does not depend on the token is requested first: the
+  // projected parent state and the LayerNorm affine
+  const float* pz = j.pz + (int64_t)parent * D;
+  float z[NCH][8], ga[NCH][8], be[NCH][8];
+#pragma unroll
+  for (int ci = 0; ci < NCH; ++ci) {
+    const int c = tid + ci * NT;
+    if (c < nchunk) {
+      const float4 p0 = *reinterpret_cast<const float4*>(pz + c * 8);
+      const float4 p1 = *reinterpret_cast<const float4*>(pz + c * 8 + 4);
+      const float4 g0 = *reinterpret_cast<const float4*>(j.gamma + c * 8);
+      const float4 g1 = *reinterpret_cast<const float4*>(j.gamma + c * 8 + 4);
+      const float4 b0 = *reinterpret_cast<const float4*>(j.beta + c * 8);
+      const float4 b1 = *reinterpret_cast<const float4*>(j.beta + c * 8 + 4);
+      z[ci][0] = p0.x; z[ci][1] = p0.y; z[ci][2] = p0.z; z[ci][3] = p0.w;
+      z[ci][4] = p1.x; z[ci][5] = p1.y; z[ci][6] = p1.z; z[ci][7] = p1.w;
+      ga[ci][0] = g0.x; ga[ci][1] = g0.y; ga[ci][2] = g0.z; ga[ci][3] = g0.w;
+      ga[ci][4] = g1.x; ga[ci][5] = g1.y; ga[ci][6] = g1.z; ga[ci][7] = g1.w;
+      be[ci][0] = b0.x; be[ci][1] = b0.y; be[ci][2] = b0.z; be[ci][3] = b0.w;
+      be[ci][4] = b1.x; be[ci][5] = b1.y; be[ci][6] = b1.z; be[ci][7] = b1.w;
+    }
+  }
+
+  int tok;
+  if (j.stage == 0) {
+    tok = j.last_tok[r];
+  } else {
+    float v[kMaxTopK];
+    int32_t ix[kMaxTopK];
+    float lse;
+    // every 256-thread group merges the same parent row (one group would do; the
+    // barriers inside need all of them anyway)
+    group_merge_partials(j.part, parent, j.nparts, j.k_prev, v, ix, lse, merge_lds);
+    tok = ix[0];
+#pragma unroll
+    for (int q = 1; q < kMaxTopK; ++q)
+      if (q == rank) tok = ix[q];
+    if (rank == 0 && tid < 64) {
+#pragma unroll
+      for (int q = 0; q < kMaxTopK; ++q)
+        if (lane == q && q < j.k_prev) {
+          store_agent(&j.prev_tok[(int64_t)parent * j.k_prev + q], ix[q]);
+          store_agent(&j.prev_logp[(int64_t)parent * j.k_prev + q], v[q] - lse);
+        }
+      if (lane == 0) store_agent(&j.prev_lse[parent], lse);
+    }
+  }
+  tok = min(max(tok, 0), j.V - 1);  // a wild token from the caller must not leave the table
+
+  // gather + mix
+  float lsum = 0.f;
+#pragma unroll
+  for (int ci = 0; ci < NCH; ++ci) {
+    const int c = tid + ci * NT;
+    if (c < nchunk) {
+      float e[8];
+      if (BF16) {
+        const uint4 raw =
+            *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(j.emb) + (int64_t)tok * D + c * 8);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          e[2 * q] = bf16_bits_to_f32(w[q] & 0xffffu);
+          e[2 * q + 1] = bf16_bits_to_f32(w[q] >> 16);
+        }
+      } else {
+        const float* er = static_cast<const float*>(j.emb) + (int64_t)tok * D + c * 8;
+        const float4 e0 = *reinterpret_cast<const float4*>(er);
+        const float4 e1 = *reinterpret_cast<const float4*>(er + 4);
+        e[0] = e0.x; e[1] = e0.y; e[2] = e0.z; e[3] = e0.w;
+        e[4] = e1.x; e[5] = e1.y; e[6] = e1.z; e[7] = e1.w;
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        z[ci][q] = j.w_s * z[ci][q] + j.w_e * e[q];
+        lsum += z[ci][q];
+      }
+    }
+  }
+  const float mean = block_sum<NT>(lsum, scratch) / (float)D;
+  float lvar = 0.f;
+#pragma unroll
+  for (int ci = 0; ci < NCH; ++ci) {
+    if (tid + ci * NT < nchunk) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const float d = z[ci][q] - mean;
+        lvar += d * d;
+      }
+    }
+  }
+  const float var = block_sum<NT>(lvar, scratch) / (float)D;
+  const float rstd = 1.0f / sqrtf(var + j.eps);
+
+#pragma unroll
+  for (int ci = 0; ci < NCH; ++ci) {
+    const int c = tid + ci * NT;
+    if (c < nchunk) {
+      float s[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const float y = (z[ci][q] - mean) * rstd * ga[ci][q] + be[ci][q];
+        s[q] = 0.5f * y * (1.0f + erff(y * 0.70710678118654752440f));
+      }
+      if (BF16) {
+        uint4 o;
+        o.x = f32_to_bf16_bits(s[0]) | (f32_to_bf16_bits(s[1]) << 16);
+        o.y = f32_to_bf16_bits(s[2]) | (f32_to_bf16_bits(s[3]) << 16);
+        o.z = f32_to_bf16_bits(s[4]) | (f32_to_bf16_bits(s[5]) << 16);
+        o.w = f32_to_bf16_bits(s[6]) | (f32_to_bf16_bits(s[7]) << 16);
+        // tiled layout: row tile r/16, column fragment c/4, lane slot (c%4)*16 + r%16
+        const int64_t slot = ((int64_t)(r >> 4) * (D / 32) + (c >> 2)) * 64 + ((c & 3) << 4) + (r & 15);
+        uint64_t* so = reinterpret_cast<uint64_t*>(j.state_out) + 2 * slot;
+        store_agent(so, (uint64_t)o.x | ((uint64_t)o.y << 32));
+        store_agent(so + 1, (uint64_t)o.z | ((uint64_t)o.w << 32));
+        if (j.state_dbg) reinterpret_cast<uint4*>(j.state_dbg)[((int64_t)r * D) / 8 + c] = o;
+      } else {
+        float* so = static_cast<float*>(j.state_out) + (int64_t)r * D + c * 8;
+        *reinterpret_cast<float4*>(so) = make_float4(s[0], s[1], s[2], s[3]);
+        *reinterpret_cast<float4*>(so + 4) = make_float4(s[4], s[5], s[6], s[7]);
+        if (j.state_dbg) {
+          float* sd = static_cast<float*>(j.state_dbg) + (int64_t)r * D + c * 8;
+          *reinterpret_cast<float4*>(sd) = make_float4(s[0], s[1], s[2], s[3]);
+          *reinterpret_cast<float4*>(sd + 4) = make_float4(s[4], s[5], s[6], s[7]);
+        }
+      }
+    }
+  }
+}
+
+// Tree step for one sequence q, by a whole workgroup of NT threads: merge the last
+// head's partial results, score every leaf by the sum of its tokens' log-probabilities
+// (added in stage order), keep the B best.
+struct TreeArgs {
+  int n, B, L, k_last, nparts;
+  int64_t off_last, row_off_last;   // the last stage's offsets in tok / logp and in lse
+  Partials part;                    // last head
+  int32_t* tok;                     // per-stage tables [R_i][k_i], concatenated
+  float* logp;
+  float* lse;
+  int32_t* cand_tokens;
+  float* cand_scores;
+  int32_t* cand_leaf;
+};
+
+// s_k / s_off: per-stage top_k and table offsets, in LDS (indexing kernel arguments with
+// a run-time stage number would make the compiler spill the argument block to scratch).
+// sc: kMaxLeaves floats of LDS; merge_lds: (NT / 256) * 32 words.
+// KWAVE: widest k_last merged one row per wave (register-hungry for wide lists: a wave
+// of a 1024-thread workgroup has 128 registers); wider ones are merged one row per
+// 256-thread group.  Contains workgroup barriers.
+template <int NT, int KWAVE>
+__device__ __forceinline__ void tree_body(const TreeArgs& j, int q, const int* s_k, const int64_t* s_off, float* sc,
+                                          float* merge_lds) {
+  const int tid = opaque_tid(), lane = tid & 63, wave = tid >> 6;
+  const int n = j.n, L = j.L, k_last = j.k_last;
+  const int rows_last = L / k_last;
+
+  if (k_last <= KWAVE) {
+    for (int rl = wave; rl < rows_last; rl += NT / 64) {
+      const int64_t row = (int64_t)q * rows_last + rl;
+      float v[kMaxTopK];
+      int32_t ix[kMaxTopK];
+      float lse;
+      if (KWAVE >= kMaxTopK) {
+        wave_merge_partials(j.part, row, j.nparts, k_last, v, ix, lse);
+      } else {
+        switch (k_last) {
+          case 1: wave_merge_partials_k<1>(j.part, row, j.nparts, k_last, v, ix, lse); break;
+          case 2: wave_merge_partials_k<2>(j.part, row, j.nparts, k_last, v, ix, lse); break;
+          case 3: wave_merge_partials_k<3>(j.part, row, j.nparts, k_last, v, ix, lse); break;
+          default: wave_merge_partials_k<4>(j.part, row, j.nparts, k_last, v, ix, lse); break;
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < kMaxTopK; ++t)
+        if (lane == t && t < k_last) {
+          j.tok[j.off_last + row * k_last + t] = ix[t];
+          j.logp[j.off_last + row * k_last + t] = v[t] - lse;
+        }
+      if (lane == 0) j.lse[j.row_off_last + row] = lse;
+    }
+  } else {
+    const int grp = tid >> 8, gl = tid & 255;
+    for (int r0 = 0; r0 < rows_last; r0 += NT / 256) {
+      const int rl = r0 + grp;
+      const bool live = rl < rows_last;
+      const int64_t row = (int64_t)q * rows_last + (live ? rl : rows_last - 1);
+      float v[kMaxTopK];
+      int32_t ix[kMaxTopK];
+      float lse;
+      group_merge_partials(j.part, row, j.nparts, k_last, v, ix, lse, merge_lds + grp * 32);
+#pragma unroll
+      for (int t = 0; t < kMaxTopK; ++t)
+        if (live && gl == t && t < k_last) {
+          j.tok[j.off_last + row * k_last + t] = ix[t];
+          j.logp[j.off_last + row * k_last + t] = v[t] - lse;
+        }
+      if (live && gl == 0) j.lse[j.row_off_last + row] = lse;
+    }
+  }
+  __threadfence_block();
+  __syncthreads();
+
+  for (int leaf = tid; leaf < L; leaf += NT) {
+    float score = 0.f;
+    int64_t row = q;
+    int stride = L;
+    for (int i = 0; i < n; ++i) {
+      const int k = s_k[i];
+      stride /= k;
+      const int rank = (leaf / stride) % k;
+      score += j.logp[s_off[i] + row * k + rank];
+      row = row * k + rank;
+    }
+    sc[leaf] = score;
+  }
+  __syncthreads();
+
+  for (int leaf = tid; leaf < L; leaf += NT) {
+    const float s = sc[leaf];
+    int pos = 0;
+    for (int o = 0; o < L; ++o) {
+      const float so = sc[o];
+      pos += ((so > s) || (so == s && o < leaf)) ? 1 : 0;
+    }
+    if (pos < j.B) {
+      const int64_t c = (int64_t)q * j.B + pos;
+      j.cand_leaf[c] = leaf;
+      j.cand_scores[c] = s;
+      int64_t row = q;
+      int stride = L;
+      for (int i = 0; i < n; ++i) {
+        const int k = s_k[i];
+        stride /= k;
+        const int rank = (leaf / stride) % k;
+        j.cand_tokens[c * n + i] = j.tok[s_off[i] + row * k + rank];
+        row = row * k + rank;
+      }
+    }
+  }
+}
+
+}  // namespace specdraft

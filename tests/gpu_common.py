@@ -10,6 +10,7 @@ import numpy as np
 import torch
 
 from oracle import spec_oracle as O
+from paper_2404_19124_amd import binding as B
 from paper_2404_19124_amd import workloads as W
 from paper_2404_19124_amd.runner import Step
 from tests import parity
@@ -32,8 +33,9 @@ def tables_to_numpy(step: Step):
 
 def run_workload(wl: W.Workload, ln_affine: str = "identity", gen_device: str = "cuda",
                  sample_seqs: Optional[Sequence[int]] = None, w_s: float = -1.0, w_e: float = -1.0,
-                 check_verify: bool = True, tied: bool = False):
-    """Returns (report, step, oracle draft, oracle verify)."""
+                 check_verify: bool = True, tied: bool = False, fused: Optional[bool] = None):
+    """Returns (report, step, oracle draft, oracle verify).  fused: None = the library's
+    choice, True / False = spec_set_fused before the draft."""
     t0 = time.time()
     log("workload %s: E=%d D=%d V=%d n=%d k=%s B=%d batch=%d dtype=%s seed=%d"
         % (wl.name, wl.emb_dim, wl.inner_dim, wl.vocab, wl.n_predict, wl.top_k, wl.B, wl.batch, wl.weight_dtype, wl.seed))
@@ -48,6 +50,8 @@ def run_workload(wl: W.Workload, ln_affine: str = "identity", gen_device: str = 
     state_d, last_d = state.cuda(), last.cuda()
 
     step = Step(wl, w_dev, debug=True, state_weight=w_s, emb_weight=w_e)
+    if fused is not None:
+        B.spec_set_fused(step.model, fused)
     step.draft(state_d, last_d)
     torch.cuda.synchronize()
     log("  HIP draft done (%.1fs)" % (time.time() - t0))

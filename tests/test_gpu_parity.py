@@ -76,6 +76,43 @@ def test_small_bf16_shapes(case):
     assert rep.rows_exempt <= 1
 
 
+# Shapes the one-launch draft takes (every stage <= 16 rows, E == D a multiple of 512 up to 4096).
+FUSED_BF16 = [
+    ("fused_d512_rows_1_5_15", 512, 512, 1000, 3, (5, 3, 2), 10, 1),    # the paper's tree shape, ragged vocabulary
+    ("fused_d1024_b2", 1024, 1024, 2049, 3, (2, 2, 2), 8, 2),           # two sequences: 2, 4, 8 rows
+    ("fused_d2048_k8", 2048, 2048, 777, 2, (8, 8), 64, 2),              # 16 rows, widest top-k, group merge in the tree
+    ("fused_d512_chain_n7", 512, 512, 500, 7, (1,) * 7, 1, 2),          # k = 1 chain, 15 barriers
+    ("fused_d3072_b1", 3072, 3072, 640, 2, (6, 2), 12, 1),
+]
+
+
+@pytest.mark.parametrize("case", FUSED_BF16, ids=[c[0] for c in FUSED_BF16])
+def test_fused_draft_matches_oracle_and_separate_launches(case):
+    name, E, D, V, n, top_k, Bc, batch = case
+    wl = W.Workload(name, E, D, V, n, top_k, Bc, batch, "bf16", "f32", 0.6, seed=17, emb_std=0.3)
+    rep_f, step_f, od, ov = run_workload(wl, ln_affine="random", gen_device="cpu", fused=True)
+    phases = B.spec_fused_phase_us(step_f.model)
+    assert len(phases) == 2 * n + 3, "the fused launch did not run: %s" % phases
+    assert all(0.0 <= p < 1e6 for p in phases), phases
+    rep_s, step_s, _, _ = run_workload(wl, ln_affine="random", gen_device="cpu", fused=False)
+    assert B.spec_fused_phase_us(step_s.model) == []
+    # same arithmetic in the same order: the two modes agree bit for bit
+    for a, b in ((step_f.cand_tokens, step_s.cand_tokens), (step_f.cand_scores, step_s.cand_scores),
+                 (step_f.cand_leaf, step_s.cand_leaf)):
+        assert torch.equal(a, b)
+    for key in ("stage_state", "topk_tok", "topk_logp", "row_lse"):
+        assert torch.equal(step_f.dbg[key], step_s.dbg[key]), key
+    # a second call on the same model (the barrier counter carries on)
+    step_f.cand_tokens.zero_()
+    gen = W.make_generator(wl.seed, "cpu")
+    W.make_speculator(wl, gen, device="cpu", ln_affine="random")
+    state, last = W.make_draft_inputs(wl, gen, device="cpu")
+    for _ in range(3):
+        step_f.draft(state.cuda(), last.cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(step_f.cand_tokens, step_s.cand_tokens)
+
+
 SMALL_F32 = [
     ("f32_b1", 256, 256, 1024, 3, (4, 3, 2), 24, 1),
     ("f32_b5", 100, 72, 333, 3, (3, 3, 2), 7, 5),           # nothing a multiple of the tile sizes
