@@ -32,7 +32,7 @@
 
 namespace specdraft {
 
-// Slab geometry: KS K-steps (of 32) per slab; global loads run PD slabs ahead of the
+// Slab geometry: KS K-steps (of 32) per slab; weight loads run PD slabs ahead of the
 // matrix cores through NSET = PD + 1 rotating register sets; a state slab is written to
 // one of NSET LDS buffers TWO slabs before it is used, so that the fragments of the next
 // slab's first K-step can be read before the barrier that closes the current slab and the
@@ -40,6 +40,12 @@ namespace specdraft {
 constexpr int KS = 2;
 constexpr int PD = 3;
 constexpr int NSET = PD + 1;
+// State slots are requested GD slabs ahead of their USE, i.e. GD - 2 slabs ahead of the
+// copy into LDS (which happens two slabs before the use): with GD = PD the copy would
+// wait for loads issued just one slab earlier, and, loads completing in order, for
+// everything issued before them.
+constexpr int GD = 4;
+static_assert(GD <= NSET, "a state register set is reused NSET slabs later");
 
 static void fill_plan(GemmPlan& pl, int R, int n_head, int n_proj, int n_cu) {
   pl.m_tiles = (R + 16 * pl.mi - 1) / (16 * pl.mi);
@@ -149,10 +155,13 @@ __global__ __launch_bounds__(256, (MI <= 4 ? 2 : 1)) void head_gemm_kernel(GemmA
 
   // Rotating register sets: weight fragments a[], state slots g[].
   u32x4 a[NSET][NI][KS], g[NSET][SPT];
-  auto load_slab = [&](u32x4 (&aw)[NI][KS], u32x4 (&gs)[SPT], int sl) {
+  auto load_g = [&](u32x4 (&gs)[SPT], int sl) {
     const int64_t off = (int64_t)sl * KS * 64;
 #pragma unroll
     for (int s = 0; s < SPT; ++s) gs[s] = sptr[s][off];
+  };
+  auto load_a = [&](u32x4 (&aw)[NI][KS], int sl) {
+    const int64_t off = (int64_t)sl * KS * 64;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
@@ -178,8 +187,11 @@ __global__ __launch_bounds__(256, (MI <= 4 ? 2 : 1)) void head_gemm_kernel(GemmA
   int nt[NI], mat = 0;
   set_tile(t0, wptr, nt, mat);
 #pragma unroll
+  for (int q = 0; q < GD; ++q)
+    if (q < nslab) load_g(g[q], q);
+#pragma unroll
   for (int q = 0; q < PD; ++q)
-    if (q < nslab) load_slab(a[q], g[q], q);
+    if (q < nslab) load_a(a[q], q);
 
   for (int t = t0; t < t1; ++t) {
     f32x4 acc[MI][NI];
@@ -210,10 +222,11 @@ __global__ __launch_bounds__(256, (MI <= 4 ? 2 : 1)) void head_gemm_kernel(GemmA
     int base = 0;
     // steady state: no branches inside, so the compiler's wait counters see
     // straight-line code and let all PD slabs of loads stay in flight
-    for (; base + NSET + PD <= nslab; base += NSET) {
+    for (; base + NSET + GD <= nslab; base += NSET) {
 #pragma unroll
       for (int u = 0; u < NSET; ++u) {
-        load_slab(a[(u + PD) % NSET], g[(u + PD) % NSET], base + u + PD);
+        load_g(g[(u + GD) % NSET], base + u + GD);
+        load_a(a[(u + PD) % NSET], base + u + PD);
         read_b(bf1, u, 1);
         mma(a[u], bf0, 0);
         store_s(g[(u + 2) % NSET], (u + 2) % NSET);
@@ -222,13 +235,14 @@ __global__ __launch_bounds__(256, (MI <= 4 ? 2 : 1)) void head_gemm_kernel(GemmA
         __syncthreads();
       }
     }
-    // tail (at most NSET + PD - 1 slabs): the same steps, guarded
+    // tail (at most NSET + GD - 1 slabs): the same steps, guarded
     for (; base < nslab; base += NSET) {
 #pragma unroll
       for (int u = 0; u < NSET; ++u) {
         const int sl = base + u;
         if (sl < nslab) {
-          if (sl + PD < nslab) load_slab(a[(u + PD) % NSET], g[(u + PD) % NSET], sl + PD);
+          if (sl + GD < nslab) load_g(g[(u + GD) % NSET], sl + GD);
+          if (sl + PD < nslab) load_a(a[(u + PD) % NSET], sl + PD);
           read_b(bf1, u, 1);
           mma(a[u], bf0, 0);
           if (sl + 2 < nslab) store_s(g[(u + 2) % NSET], (u + 2) % NSET);
@@ -247,8 +261,11 @@ __global__ __launch_bounds__(256, (MI <= 4 ? 2 : 1)) void head_gemm_kernel(GemmA
     if (t + 1 < t1) {
       set_tile(t + 1, wptr, nt, mat);
 #pragma unroll
+      for (int q = 0; q < GD; ++q)
+        if (q < nslab) load_g(g[q], q);
+#pragma unroll
       for (int q = 0; q < PD; ++q)
-        if (q < nslab) load_slab(a[q], g[q], q);
+        if (q < nslab) load_a(a[q], q);
     }
 
     // ---- epilogue of tile t
@@ -379,6 +396,359 @@ __global__ __launch_bounds__(256, (MI <= 4 ? 2 : 1)) void head_gemm_kernel(GemmA
   }
 }
 
+// Instruction pattern of one half of a slab in the wide kernel: N_MFMA matrix
+// instructions with the half's memory instructions (LDS reads first, then global loads,
+// then LDS writes) spread evenly behind them.  A wave issues in order, and a memory
+// instruction takes several issue cycles: grouped in front of the matrix instructions
+// they leave the matrix core idle (measured: 1320 cycles per slab against 980 when
+// interleaved, 740 being the matrix work alone).
+template <int N_MFMA, int N_DSR, int N_VMEM, int N_DSW>
+__device__ __forceinline__ void interleave_half() {
+  constexpr int TOTAL = N_DSR + N_VMEM + N_DSW;
+#pragma unroll
+  for (int i = 0; i < N_MFMA; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+#pragma unroll
+    for (int j = i * TOTAL / N_MFMA; j < (i + 1) * TOTAL / N_MFMA; ++j) {
+      if (j < N_DSR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                // one LDS read
+      else if (j < N_DSR + N_VMEM) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // one global load
+      else __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                          // one LDS write
+    }
+  }
+}
+
+// Wide blocks: the same kernel built on v_mfma_f32_32x32x16_bf16.  One wave per SIMD can
+// keep the matrix cores busy with the 32x32 instruction (measured: 2.1 PFLOP/s in a bare
+// loop) but not with the 16x16 one (1.46 PFLOP/s: it needs a second wave per SIMD, and
+// the wide tile leaves no registers for one).  The operands are gathered from the SAME
+// tiled layout: a 32-row operand for K sub-step s of a 32-wide K step takes, for lane
+// (row c = lane % 32, K half h = lane / 32), the 16-byte slot (2 s + h) * 16 + c % 16 of
+// the 16-row tile pair member c / 16: four contiguous 256-byte pieces per wave load.
+// Weights and states use the same assignment of K to lanes, which is all the contraction
+// needs.  A lane then holds, for state row c of block mb, the logits of weight rows
+// 32 nb + 4 h + 8 q + r (accumulator entry 4 q + r), in increasing vocabulary order.
+// MB / NB = 32-row blocks of states per workgroup / of weight rows per wave.
+template <int MB, int NB, int KT>
+__global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
+  constexpr int MI = 2 * MB, NI = 2 * NB;  // in 16-row tiles of the layout
+  extern __shared__ __align__(16) unsigned char smem[];
+  u32x4* ldsB = reinterpret_cast<u32x4*>(smem);  // [NSET][MI*KS*64]
+  constexpr int SLAB = MI * KS * 64;             // slots per slab
+  constexpr int SPT = SLAB / 256;                // staging slots per thread
+  static_assert(SLAB % 256 == 0, "a slab is staged by whole passes of the workgroup");
+  static_assert(KS == 2, "the K loop below is written for two K-steps per slab");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c32 = lane & 31, half = lane >> 5;
+
+  // XCD-aware workgroup id: hardware places workgroup ids round-robin over 8 XCDs
+  const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+  if (seq >= p.chunk) return;
+  const int wg = xcd * p.chunk + seq;
+  if (wg >= p.m_tiles * p.n_ranges) return;
+  const int range = wg / p.m_tiles, mtile = wg - range * p.m_tiles;
+  const int total_tiles = p.n_tiles[0] + p.n_tiles[1];
+  const int t0 = (int)((int64_t)range * total_tiles / p.n_ranges);
+  const int t1 = (int)((int64_t)(range + 1) * total_tiles / p.n_ranges);
+
+  const int kt = p.kt;
+  const int nslab = kt / KS;
+  // staging sources of this thread (the same for every tile of the range)
+  const u32x4* sptr[SPT];
+#pragma unroll
+  for (int s = 0; s < SPT; ++s) {
+    const int i = s * 256 + tid;
+    const int mtl = i / (KS * 64), rem = i % (KS * 64);
+    const int mt = min(mtile * MI + mtl, p.mt_total - 1);
+    sptr[s] = p.b + (int64_t)mt * kt * 64 + rem;
+  }
+
+  // weight fragment pointers of this wave for a given tile of the list
+  const u32x4* wptr[NB];
+  auto set_tile = [&](int t, const u32x4* (&wp)[NB], int (&ntv)[NB], int& mat) {
+    mat = t >= p.n_tiles[0] ? 1 : 0;
+    const int ntile = t - (mat ? p.n_tiles[0] : 0);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      ntv[nb] = (ntile * 4 + wave) * NI + 2 * nb;  // first 16-row tile of the block (even)
+      const int ntc = min(ntv[nb] + (c32 >> 4), p.nt_total[mat] - 1);
+      wp[nb] = p.w[mat] + (int64_t)ntc * kt * 64 + half * 16 + (c32 & 15);
+    }
+  };
+
+  // Rotating register sets: weight fragments a[], state slots g[].
+  u32x4 a[NSET][NB][2 * KS], g[NSET][SPT];
+  auto load_g = [&](u32x4 (&gs)[SPT], int sl) {
+    const int64_t off = (int64_t)sl * KS * 64;
+#pragma unroll
+    for (int s = 0; s < SPT; ++s) gs[s] = sptr[s][off];
+  };
+  auto load_a1 = [&](u32x4 (&aw)[NB][2 * KS], int sl, int nb) {
+    const int64_t off = (int64_t)sl * KS * 64;
+#pragma unroll
+    for (int q = 0; q < 2 * KS; ++q) aw[nb][q] = wptr[nb][off + q * 32];  // q = 2 * K-step + sub-step
+  };
+  auto load_a = [&](u32x4 (&aw)[NB][2 * KS], int sl) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) load_a1(aw, sl, nb);
+  };
+  auto store_s = [&](const u32x4 (&gs)[SPT], int buf) {
+#pragma unroll
+    for (int s = 0; s < SPT; ++s) ldsB[buf * SLAB + s * 256 + tid] = gs[s];
+  };
+
+  // running softmax / top-k state of this lane, per state row (mi, col)
+  float run_m[MB], run_s[MB], lv[MB][KT];
+  int32_t li[MB][KT];
+#pragma unroll
+  for (int mi = 0; mi < MB; ++mi) {
+    run_m[mi] = SPEC_NEG_INF;
+    run_s[mi] = 0.f;
+#pragma unroll
+    for (int q = 0; q < KT; ++q) { lv[mi][q] = SPEC_NEG_INF; li[mi][q] = kIdxNone; }
+  }
+  bool any_head = false;
+
+  int nt[NB], mat = 0;
+  set_tile(t0, wptr, nt, mat);
+#pragma unroll
+  for (int q = 0; q < GD; ++q)
+    if (q < nslab) load_g(g[q], q);
+#pragma unroll
+  for (int q = 0; q < PD; ++q)
+    if (q < nslab) load_a(a[q], q);
+
+  for (int t = t0; t < t1; ++t) {
+    f32x16 acc[MB][NB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[mb][nb][e] = 0.f;
+    // state operands of one 32-wide K step: [sub-step][block]
+    auto read_b = [&](u32x4 (&bf)[2 * MB], int buf, int ts) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+          bf[s * MB + mb] =
+              ldsB[buf * SLAB + ((2 * mb + (c32 >> 4)) * KS + ts) * 64 + (2 * s + half) * 16 + (c32 & 15)];
+    };
+    auto mma = [&](const u32x4 (&aw)[NB][2 * KS], const u32x4 (&bf)[2 * MB], int ts) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb)
+            acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw[nb][2 * ts + s]),
+                                                                  __builtin_bit_cast(bf16x8, bf[s * MB + mb]),
+                                                                  acc[mb][nb], 0, 0, 0);
+    };
+
+    // ---- K loop (slab sl uses register set and LDS buffer sl % NSET; the loop is
+    // unrolled NSET times so every index is a constant)
+    store_s(g[0], 0);
+    if (nslab > 1) store_s(g[1], 1);
+    __syncthreads();
+    u32x4 bf0[2 * MB], bf1[2 * MB];
+    read_b(bf0, 0, 0);
+    int base = 0;
+    // steady state (whole groups of NSET slabs): no branches inside, so the compiler's
+    // wait counters see straight-line code and let all the loads stay in flight.  Loads
+    // that would run past the tile's last slab fetch that slab again (nobody uses them).
+    for (; base + NSET <= nslab; base += NSET) {
+#pragma unroll
+      for (int u = 0; u < NSET; ++u) {
+        const int sl_g = min(base + u + GD, nslab - 1), sl_a = min(base + u + PD, nslab - 1);
+        // first half: K step 0 of the slab; behind its matrix instructions: the state
+        // operands of K step 1, the state slots GD slabs ahead, the first weight block PD ahead
+        read_b(bf1, u, 1);
+        load_g(g[(u + GD) % NSET], sl_g);
+        load_a1(a[(u + PD) % NSET], sl_a, 0);
+        mma(a[u], bf0, 0);
+        interleave_half<2 * NB * MB, 2 * MB, SPT + 2 * KS, 0>();
+        __builtin_amdgcn_sched_barrier(0);
+        // second half: K step 1; behind it: the next slab's first state operands, the
+        // other weight blocks, the copy of the slab two ahead into LDS
+        read_b(bf0, (u + 1) % NSET, 0);
+#pragma unroll
+        for (int nb = 1; nb < NB; ++nb) load_a1(a[(u + PD) % NSET], sl_a, nb);
+        store_s(g[(u + 2) % NSET], (u + 2) % NSET);
+        mma(a[u], bf1, 1);
+        interleave_half<2 * NB * MB, 2 * MB, (NB - 1) * 2 * KS, SPT>();
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+      }
+    }
+    // tail (fewer than NSET slabs): the same steps, guarded
+    for (; base < nslab; base += NSET) {
+#pragma unroll
+      for (int u = 0; u < NSET; ++u) {
+        const int sl = base + u;
+        if (sl < nslab) {
+          if (sl + GD < nslab) load_g(g[(u + GD) % NSET], sl + GD);
+          if (sl + PD < nslab) load_a(a[(u + PD) % NSET], sl + PD);
+          read_b(bf1, u, 1);
+          __builtin_amdgcn_sched_barrier(0);
+          mma(a[u], bf0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if (sl + 2 < nslab) store_s(g[(u + 2) % NSET], (u + 2) % NSET);
+          if (sl + 1 < nslab) read_b(bf0, (u + 1) % NSET, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          mma(a[u], bf1, 1);
+          __builtin_amdgcn_sched_barrier(0);
+          __syncthreads();
+        }
+      }
+    }
+
+    // ---- the next tile's first slabs are requested before the epilogue runs
+    const int cur_mat = mat;
+    int cur_nt[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) cur_nt[nb] = nt[nb];
+    if (t + 1 < t1) {
+      set_tile(t + 1, wptr, nt, mat);
+#pragma unroll
+      for (int q = 0; q < GD; ++q)
+        if (q < nslab) load_g(g[q], q);
+#pragma unroll
+      for (int q = 0; q < PD; ++q)
+        if (q < nslab) load_a(a[q], q);
+    }
+
+    // ---- epilogue of tile t
+    const int n_valid = p.n_valid[cur_mat];
+    if (cur_mat == 1 || p.mode0 == 1) {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const int r = (mtile * MB + mb) * 32 + c32;
+        if (r >= p.R) continue;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int v0 = cur_nt[nb] * 16 + half * 4 + 8 * q;
+            float* o = p.out[cur_mat] + (int64_t)r * p.ldo[cur_mat] + v0;
+            if (v0 + 3 < n_valid && (p.ldo[cur_mat] & 3) == 0) {
+              *reinterpret_cast<float4*>(o) = make_float4(acc[mb][nb][4 * q], acc[mb][nb][4 * q + 1],
+                                                          acc[mb][nb][4 * q + 2], acc[mb][nb][4 * q + 3]);
+            } else {
+#pragma unroll
+              for (int i = 0; i < 4; ++i)
+                if (v0 + i < n_valid) o[i] = acc[mb][nb][4 * q + i];
+            }
+          }
+      }
+    } else {
+      any_head = true;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        // this lane's 16*NB logits of state row (mb, c32), in increasing vocabulary order
+        float x[NB * 16];
+        float tmax = SPEC_NEG_INF;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int v = cur_nt[nb] * 16 + half * 4 + 8 * (e >> 2) + (e & 3);
+            const float xv = v < n_valid ? acc[mb][nb][e] : SPEC_NEG_INF;
+            x[nb * 16 + e] = xv;
+            tmax = fmaxf(tmax, xv);
+          }
+        const float new_m = fmaxf(run_m[mb], tmax);
+        if (new_m > SPEC_NEG_INF) {
+          float s = run_s[mb] * __expf(run_m[mb] - new_m);
+#pragma unroll
+          for (int e = 0; e < NB * 16; ++e) s += __expf(x[e] - new_m);
+          run_s[mb] = s;
+          run_m[mb] = new_m;
+        }
+        if (tmax > lv[mb][KT - 1]) {   // rare once the list has warmed up
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const float xv = x[nb * 16 + e];
+              if (xv > lv[mb][KT - 1]) {
+                // a later vocabulary entry of equal value loses the tie: strict compares
+                float cv = xv;
+                int32_t ci = cur_nt[nb] * 16 + half * 4 + 8 * (e >> 2) + (e & 3);
+#pragma unroll
+                for (int q = 0; q < KT; ++q) {
+                  const bool gt = cv > lv[mb][q];
+                  const float ov = lv[mb][q];
+                  const int32_t oi = li[mb][q];
+                  lv[mb][q] = gt ? cv : ov;
+                  li[mb][q] = gt ? ci : oi;
+                  cv = gt ? ov : cv;
+                  ci = gt ? oi : ci;
+                }
+              }
+            }
+        }
+      }
+    }
+  }
+
+  if (!any_head) return;
+
+  // ---- merge the 8 lane lists of every row (2 K halves x 4 waves) into the workgroup's
+  // partial.  LDS aliases the slabs: the K loop ended on a barrier.
+  constexpr int ROWS = 32 * MB;
+  float* sv = reinterpret_cast<float*>(smem);                  // [256][MB][KT]
+  int32_t* si = reinterpret_cast<int32_t*>(sv + 256 * MB * KT);
+  float* sm = reinterpret_cast<float*>(si + 256 * MB * KT);    // [256][MB]
+  float* ss = sm + 256 * MB;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+    for (int q = 0; q < KT; ++q) {
+      sv[(tid * MB + mb) * KT + q] = lv[mb][q];
+      si[(tid * MB + mb) * KT + q] = li[mb][q];
+    }
+    sm[tid * MB + mb] = run_m[mb];
+    ss[tid * MB + mb] = run_s[mb];
+  }
+  __syncthreads();
+  for (int rl = tid; rl < ROWS; rl += 256) {
+    const int r = mtile * ROWS + rl;
+    if (r >= p.R) continue;
+    const int mb = rl >> 5, c = rl & 31;
+    float mx = SPEC_NEG_INF;
+    for (int src = 0; src < 8; ++src) mx = fmaxf(mx, sm[(src * 32 + c) * MB + mb]);
+    float s = 0.f;
+    for (int src = 0; src < 8; ++src) {
+      const int th = src * 32 + c;
+      const float m = sm[th * MB + mb];
+      if (m > SPEC_NEG_INF) s += ss[th * MB + mb] * __expf(m - mx);
+    }
+    const int64_t slot = (int64_t)r * p.nparts + range;
+    p.part.m[slot] = mx;
+    p.part.s[slot] = s;
+    // 8-way merge of sorted lists: only the heads compete; 4-bit read positions packed in one word
+    uint32_t pos = 0;
+    for (int j = 0; j < p.k_top; ++j) {
+      float bv = SPEC_NEG_INF;
+      int32_t bi = kIdxNone;
+      int bsrc = 0;
+      for (int src = 0; src < 8; ++src) {
+        const int q = (int)((pos >> (4 * src)) & 15);
+        if (q < KT) {
+          const int th = src * 32 + c;
+          const float v = sv[(th * MB + mb) * KT + q];
+          const int32_t i = si[(th * MB + mb) * KT + q];
+          if (before(v, i, bv, bi)) { bv = v; bi = i; bsrc = src; }
+        }
+      }
+      pos += 1u << (4 * bsrc);
+      p.part.val[slot * p.k_top + j] = bv;
+      p.part.idx[slot * p.k_top + j] = bi;
+    }
+  }
+}
+
 static size_t gemm_smem(int mi, int kcap) {
   const size_t slabs = (size_t)NSET * mi * KS * 64 * 16;
   const size_t merge = (size_t)256 * mi * (kcap * 8 + 8);
@@ -396,6 +766,21 @@ static hipError_t launch_gemm_t(const GemmArgs& a, hipStream_t st, hipEvent_t ev
     attr_set = true;
   }
   hipExtLaunchKernelGGL((head_gemm_kernel<MI, NI, KT>), dim3(a.chunk * 8), dim3(256), smem, st, ev_start, ev_stop, 0, a);
+  return hipGetLastError();
+}
+
+template <int MB, int NB, int KT>
+static hipError_t launch_gemm32_t(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
+  const size_t smem = gemm_smem(2 * MB, KT);
+  static bool attr_set = false;  // per instantiation
+  if (!attr_set && smem > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_gemm32_kernel<MB, NB, KT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipExtLaunchKernelGGL((head_gemm32_kernel<MB, NB, KT>), dim3(a.chunk * 8), dim3(256), smem, st, ev_start, ev_stop, 0,
+                        a);
   return hipGetLastError();
 }
 
@@ -440,8 +825,8 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
   switch (key) {
     case 2 * 100 + 1 * 10 + 8: return launch_gemm_t<2, 1, 8>(a, st, ev_start, ev_stop);
     case 4 * 100 + 1 * 10 + 8: return launch_gemm_t<4, 1, 8>(a, st, ev_start, ev_stop);
-    case 6 * 100 + 4 * 10 + 2: return launch_gemm_t<6, 4, 2>(a, st, ev_start, ev_stop);
-    case 6 * 100 + 4 * 10 + 4: return launch_gemm_t<6, 4, 4>(a, st, ev_start, ev_stop);
+    case 6 * 100 + 4 * 10 + 2: return launch_gemm32_t<3, 2, 2>(a, st, ev_start, ev_stop);
+    case 6 * 100 + 4 * 10 + 4: return launch_gemm32_t<3, 2, 4>(a, st, ev_start, ev_stop);
     default: return hipErrorInvalidValue;
   }
 }

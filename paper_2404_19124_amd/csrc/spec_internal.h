@@ -12,6 +12,7 @@ constexpr int kMaxLeaves = 4096;  // = SPEC_MAX_LEAVES
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 // 16 raw bytes as a native vector (HIP's uint4 is a struct: copies of it can become
 // memcpy calls that keep small arrays out of registers)
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
