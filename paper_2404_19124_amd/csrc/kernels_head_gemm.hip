@@ -53,7 +53,7 @@ static void fill_plan(GemmPlan& pl, int R, int n_head, int n_proj, int n_cu) {
   const int nt_proj = (n_proj + 64 * pl.ni - 1) / (64 * pl.ni);
   const int total = nt_head + nt_proj;
   // narrow blocks are bandwidth-bound and light on registers: two workgroups per CU keep more loads in flight
-  int nr = (pl.mi <= 4 ? 2 : 1) * (n_cu > 0 ? n_cu : 256) / pl.m_tiles;
+  int nr = (pl.ni == 1 ? 2 : 1) * (n_cu > 0 ? n_cu : 256) / pl.m_tiles;
   if (nr < 1) nr = 1;
   if (nr > total) nr = total;
   pl.n_ranges = nr;
@@ -66,6 +66,11 @@ static void fill_plan(GemmPlan& pl, int R, int n_head, int n_proj, int n_cu) {
 GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
   GemmPlan pl;
   if (R <= 32) { pl.mi = 2; pl.ni = 1; pl.kcap = 8; }
+  // 33..64 rows against a long weight matrix (at least one 256-row tile per two CUs): the
+  // wide kernel re-reads the states a quarter as often per weight byte as the narrow one
+  else if (R <= 64 && (int64_t)n_head + n_proj >= (int64_t)128 * (n_cu > 0 ? n_cu : 256)) {
+    pl.mi = 4; pl.ni = 4; pl.kcap = 8;
+  }
   else if (R <= 64 || k_top > 4) { pl.mi = 4; pl.ni = 1; pl.kcap = 8; }
   else {
     // state-row block of 96 or 128 rows: the one whose busiest workgroup does the least
@@ -643,6 +648,9 @@ __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
       }
     } else {
       any_head = true;
+      // only the tile that holds the end of the vocabulary needs the validity mask
+      const bool edge = (cur_nt[NB - 1] + 2) * 16 > n_valid;
+      constexpr float kLog2e = 1.4426950408889634f;
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
         // this lane's 16*NB logits of state row (mb, c32), in increasing vocabulary order
@@ -653,15 +661,17 @@ __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
             const int v = cur_nt[nb] * 16 + half * 4 + 8 * (e >> 2) + (e & 3);
-            const float xv = v < n_valid ? acc[mb][nb][e] : SPEC_NEG_INF;
+            const float xv = (!edge || v < n_valid) ? acc[mb][nb][e] : SPEC_NEG_INF;
             x[nb * 16 + e] = xv;
             tmax = fmaxf(tmax, xv);
           }
         const float new_m = fmaxf(run_m[mb], tmax);
         if (new_m > SPEC_NEG_INF) {
-          float s = run_s[mb] * __expf(run_m[mb] - new_m);
+          // exp(x - m) as exp2(x * log2(e) - m * log2(e)): one fused multiply-add per logit
+          const float ml = new_m * kLog2e;
+          float s = run_s[mb] * __builtin_amdgcn_exp2f((run_m[mb] - new_m) * kLog2e);
 #pragma unroll
-          for (int e = 0; e < NB * 16; ++e) s += __expf(x[e] - new_m);
+          for (int e = 0; e < NB * 16; ++e) s += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], kLog2e, -ml));
           run_s[mb] = s;
           run_m[mb] = new_m;
         }
@@ -825,6 +835,7 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
   switch (key) {
     case 2 * 100 + 1 * 10 + 8: return launch_gemm_t<2, 1, 8>(a, st, ev_start, ev_stop);
     case 4 * 100 + 1 * 10 + 8: return launch_gemm_t<4, 1, 8>(a, st, ev_start, ev_stop);
+    case 4 * 100 + 4 * 10 + 8: return launch_gemm32_t<2, 2, 8>(a, st, ev_start, ev_stop);
     case 6 * 100 + 4 * 10 + 2: return launch_gemm32_t<3, 2, 2>(a, st, ev_start, ev_stop);
     case 6 * 100 + 4 * 10 + 4: return launch_gemm32_t<3, 2, 4>(a, st, ev_start, ev_stop);
     default: return hipErrorInvalidValue;

@@ -64,6 +64,7 @@ SMALL_BF16 = [
     ("bf16_b2_n4", 64, 64, 300, 4, (3, 2, 2, 2), 24, 2),    # 2, 6, 12, 24  four stages
     ("bf16_chain_n7", 128, 128, 500, 7, (1,) * 7, 1, 2),    # k = 1 chain, 7 heads
     ("bf16_b1_n5", 128, 128, 500, 5, (2, 2, 1, 2, 1), 5, 1),
+    ("bf16_b40_long_vocab", 64, 64, 33000, 2, (2, 2), 4, 40),  # 40, 80 rows: wide kernel with 64-row blocks
 ]
 
 
