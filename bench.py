@@ -30,10 +30,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
-# labels of spec_launch_record_t.kernel (first template argument of head_gemm_kernel = 16-row
-# fragments per state block)
-KERNEL_NAMES = {0: "head_skinny_kernel", 1: "head_gemm_kernel<2,...>", 2: "head_gemm_kernel<4,...>",
-                3: "head_gemm_kernel<6,...>", 4: "draft_fused_kernel"}
+# labels of spec_launch_record_t.kernel (template arguments: state-row blocks per workgroup,
+# weight-row blocks per wave, capacity of the per-lane top-k lists)
+KERNEL_NAMES = {0: "head_skinny_kernel", 1: "head_gemm_kernel<2,1,8>",
+                2: "head_gemm_kernel<4,1,8> | head_gemm32_kernel<2,2,8>", 3: "head_gemm32_kernel<3,2,*>",
+                4: "draft_fused_kernel"}
 
 
 def main() -> int:
