@@ -75,13 +75,20 @@ class Workload:
         return head + proj
 
 
-# The five configurations of the build's baseline description, in order.
+# The five configurations of the build's baseline description, in order, then the code-model shapes.
 WORKLOADS: Dict[str, Workload] = {
     "tiny_b1": Workload("tiny_b1", 256, 256, 1024, 3, (4, 3, 2), 24, 1, "f32", "f32", 0.6),
     "llama7b_b1": Workload("llama7b_b1", 4096, 4096, 32000, 3, (5, 3, 2), 16, 1, "bf16", "f32", 0.6),
     "llama7b_b64": Workload("llama7b_b64", 4096, 4096, 32000, 3, (5, 3, 2), 16, 64, "bf16", "f32", 0.6),
     "llama13b_b16": Workload("llama13b_b16", 5120, 4096, 32000, 3, (6, 4, 3), 32, 16, "bf16", "f32", 0.5),
     "large70b_b32": Workload("large70b_b32", 8192, 3072, 128256, 4, (6, 4, 3, 2), 64, 32, "bf16", "bf16", 0.5),
+    # Code-model shapes (Sec. 4.3, 4.4 of the paper): 7 heads on a 5120-wide base with a 32016-token
+    # vocabulary, 5 heads on a 6144-wide base with 49152 tokens; k = 1 chains (the setting the paper
+    # finds best on a loaded server) and a small tree.  Code is predictable: high acceptance rate.
+    "code13b_k1_b1": Workload("code13b_k1_b1", 5120, 4096, 32016, 7, (1,) * 7, 1, 1, "bf16", "f32", 0.8),
+    "code13b_tree_b4": Workload("code13b_tree_b4", 5120, 4096, 32016, 7, (2, 2, 1, 1, 1, 1, 1), 4, 4, "bf16", "f32",
+                                0.8),
+    "code20b_k1_b8": Workload("code20b_k1_b8", 6144, 4096, 49152, 5, (1,) * 5, 1, 8, "bf16", "f32", 0.8),
 }
 
 

@@ -38,3 +38,23 @@ def test_llama13b_batch16():
 def test_large70b_batch32_sampled():
     rep, *_ = run_workload(W.WORKLOADS["large70b_b32"], sample_seqs=[0, 31])
     assert rep.rows_exempt <= 2
+
+
+# ---- code-model shapes: 7 and 5 heads, k = 1 chains and a small tree (Sec. 4.3, 4.4)
+
+def test_code13b_seven_heads_chain_batch1():
+    wl = W.WORKLOADS["code13b_k1_b1"]
+    rep, step, od, _ = run_workload(wl)
+    assert rep.rows_checked + rep.rows_skipped_below_exempt == 7
+    assert rep.rows_exempt <= 1
+    assert step.cand_tokens.shape == (1, 1, 7)
+
+
+def test_code13b_seven_heads_small_tree_batch4():
+    rep, *_ = run_workload(W.WORKLOADS["code13b_tree_b4"], ln_affine="random")
+    assert rep.rows_exempt <= 2
+
+
+def test_code20b_five_heads_chain_batch8():
+    rep, *_ = run_workload(W.WORKLOADS["code20b_k1_b8"], sample_seqs=[0, 3, 7])
+    assert rep.rows_exempt <= 1
