@@ -71,7 +71,8 @@ typedef struct {
  *   head[i]     [V, D]                          weight_dtype   vocabulary head
  *   ln_gamma[i] [D], ln_beta[i] [D]             float32        LayerNorm affine
  * The paper ties nothing across stages (Sec. 3.1); passing the same pointer for
- * several stages gives its weight-tied (RNN) variant.
+ * several stages gives its weight-tied (RNN) variant (stages given the same proj / head
+ * pointer, with the same shape, share one library copy).
  * Ownership: proj and head are COPIED by spec_create into library-owned buffers
  * (for SPEC_BF16 in a tiled layout that matches the matrix-core operand order),
  * the caller may release them once spec_create has returned.  emb, ln_gamma and

@@ -226,17 +226,33 @@ extern "C" spec_status_t spec_create(const spec_config_t* cfg, const spec_weight
     m->emb[i] = w->emb[i];
     m->gamma[i] = w->ln_gamma[i];
     m->beta[i] = w->ln_beta[i];
+    // weight-tied stages (the same caller tensor given for several stages) share one copy
+    int same_proj = -1, same_head = -1;
+    for (int j = 0; j < i; ++j) {
+      if (w->proj[j] == w->proj[i] && (j == 0 ? E : D) == in && same_proj < 0) same_proj = j;
+      if (w->head[j] == w->head[i] && same_head < 0) same_head = j;
+    }
+    if (same_proj >= 0) m->proj[i] = m->proj[same_proj];
+    if (same_head >= 0) m->head[i] = m->head[same_head];
     if (m->bf16) {
       const size_t pb = (size_t)((D + 15) / 16) * 16 * in * 2, hb = (size_t)((V + 15) / 16) * 16 * D * 2;
-      TRY_FREE(dev_alloc(m, &m->proj[i], pb));
-      TRY_FREE(dev_alloc(m, &m->head[i], hb));
-      HIP_TRY_FREE(launch_pack_bf16(w->proj[i], m->proj[i], D, in, true, stream));
-      HIP_TRY_FREE(launch_pack_bf16(w->head[i], m->head[i], V, D, true, stream));
+      if (same_proj < 0) {
+        TRY_FREE(dev_alloc(m, &m->proj[i], pb));
+        HIP_TRY_FREE(launch_pack_bf16(w->proj[i], m->proj[i], D, in, true, stream));
+      }
+      if (same_head < 0) {
+        TRY_FREE(dev_alloc(m, &m->head[i], hb));
+        HIP_TRY_FREE(launch_pack_bf16(w->head[i], m->head[i], V, D, true, stream));
+      }
     } else {
-      TRY_FREE(dev_alloc(m, &m->proj[i], (size_t)D * in * 4));
-      TRY_FREE(dev_alloc(m, &m->head[i], (size_t)V * D * 4));
-      HIP_TRY_FREE(hipMemcpyAsync(m->proj[i], w->proj[i], (size_t)D * in * 4, hipMemcpyDeviceToDevice, stream));
-      HIP_TRY_FREE(hipMemcpyAsync(m->head[i], w->head[i], (size_t)V * D * 4, hipMemcpyDeviceToDevice, stream));
+      if (same_proj < 0) {
+        TRY_FREE(dev_alloc(m, &m->proj[i], (size_t)D * in * 4));
+        HIP_TRY_FREE(hipMemcpyAsync(m->proj[i], w->proj[i], (size_t)D * in * 4, hipMemcpyDeviceToDevice, stream));
+      }
+      if (same_head < 0) {
+        TRY_FREE(dev_alloc(m, &m->head[i], (size_t)V * D * 4));
+        HIP_TRY_FREE(hipMemcpyAsync(m->head[i], w->head[i], (size_t)V * D * 4, hipMemcpyDeviceToDevice, stream));
+      }
     }
   }
 
