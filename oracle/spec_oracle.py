@@ -325,3 +325,63 @@ def logp_along_path(weights: dict, state_row: np.ndarray, last_tok: int, path: S
         s = stage_state(pz, e, weights["ln_gamma"][i], weights["ln_beta"][i], w_s, w_e, eps, state_dtype)
         logp, _ = log_softmax(head_logits(s, weights["head"][i]))
     return s[0], logp[0]
+
+
+# ---------------------------------------------------------------------------
+# Widening beyond one step: token tree of the candidates, and the hand-over to
+# the next step.
+# ---------------------------------------------------------------------------
+def tree_metadata(cand_tokens: np.ndarray) -> dict:
+    """Sec. 3.1 (multi-candidate decoding with tree attention): the B candidates of a
+    sequence are root-to-leaf paths that share prefixes; a base model that evaluates
+    them as ONE tree needs every distinct prefix once.  The paper names the technique
+    only; the encoding is this build's (bit-exact contract with the device):
+
+      * a node = a distinct prefix cand[c, :p+1]; nodes are numbered in order of first
+        appearance when the candidates are scanned c = 0..B-1, p = 0..n-1;
+      * node_tok = last token of the prefix, node_depth = p + 1, node_parent = node of
+        the prefix one shorter (-1 at depth 1: the parent is the sequence's last real token);
+      * cand_node[c, p] = node of cand[c, :p+1];
+      * mask[i, j] = 1 iff node j is node i or one of its ancestors.
+    Arrays are sized M = B * n per sequence; unused entries are -1 (0 for depth, mask).
+    """
+    cand = np.asarray(cand_tokens)
+    b, B, n = cand.shape
+    M = B * n
+    out = {
+        "node_tok": np.full((b, M), -1, np.int32), "node_parent": np.full((b, M), -1, np.int32),
+        "node_depth": np.zeros((b, M), np.int32), "n_nodes": np.zeros((b,), np.int32),
+        "cand_node": np.full((b, B, n), -1, np.int32), "mask": np.zeros((b, M, M), np.uint8),
+    }
+    for q in range(b):
+        seen = {}
+        for c in range(B):
+            for p in range(n):
+                key = tuple(int(t) for t in cand[q, c, :p + 1])
+                if key not in seen:
+                    i = len(seen)
+                    seen[key] = i
+                    out["node_tok"][q, i] = key[-1]
+                    out["node_depth"][q, i] = p + 1
+                    out["node_parent"][q, i] = -1 if p == 0 else seen[key[:-1]]
+                out["cand_node"][q, c, p] = seen[key]
+        out["n_nodes"][q] = len(seen)
+        for i in range(len(seen)):
+            j = i
+            while j >= 0:
+                out["mask"][q, i, j] = 1
+                j = int(out["node_parent"][q, j])
+    return out
+
+
+def advance(hidden: np.ndarray, best_cand: np.ndarray, accept_len: np.ndarray, out_tokens: np.ndarray):
+    """Sec. 3.1 (the base model is stage 0 of the next draft): the next step starts from the
+    base model's state vector at the last position whose prediction was kept, i.e. position
+    a = accept_len of the best candidate, and from the token predicted there (the bonus token,
+    out_tokens[a]).  hidden [b, B, n+1, E] -> (next_state [b, E], next_tok [b])."""
+    hidden = np.asarray(hidden)
+    b = hidden.shape[0]
+    idx = np.arange(b)
+    a = np.asarray(accept_len).astype(np.int64)
+    return hidden[idx, np.asarray(best_cand).astype(np.int64), a, :].copy(), \
+        np.asarray(out_tokens)[idx, a].astype(np.int32)
