@@ -177,6 +177,36 @@ spec_status_t spec_profile_enable(spec_model_t* m, int32_t capacity);
  * order, stores their number in *n (host) and clears the recording. */
 spec_status_t spec_profile_read(spec_model_t* m, spec_launch_record_t* out, int32_t cap, int32_t* n);
 
+/* Token tree of the candidates (Sec. 3.1: the candidates are evaluated simultaneously with
+ * tree attention, which needs every shared prefix once).  Per sequence, with M = B * n_predict:
+ *   a node is a distinct prefix cand[c, :p+1]; nodes are numbered in order of first appearance
+ *   when the candidates are scanned c = 0..B-1, p = 0..n_predict-1.
+ *   node_tok    dev [batch, M] int32  last token of the node's prefix        (-1 past n_nodes)
+ *   node_parent dev [batch, M] int32  node of the prefix one shorter; -1 at depth 1 (-1 past n_nodes)
+ *   node_depth  dev [batch, M] int32  p + 1                                  (0 past n_nodes)
+ *   n_nodes     dev [batch]    int32  number of nodes
+ *   cand_node   dev [batch, B, n_predict] int32  node of cand[c, :p+1]
+ *   mask        dev [batch, M, M] uint8, may be NULL: mask[i, j] = 1 iff node j is node i or an
+ *               ancestor of it; 0 elsewhere (also past n_nodes)
+ * cand_tokens dev [batch, B, n_predict] int32 (as written by spec_draft).  All outputs caller-owned.
+ * B * n_predict <= 4096.  Asynchronous on hip_stream. */
+spec_status_t spec_tree_metadata(const int32_t* cand_tokens, int32_t batch, int32_t B, int32_t n_predict,
+                                 int32_t* node_tok, int32_t* node_parent, int32_t* node_depth, int32_t* n_nodes,
+                                 int32_t* cand_node, uint8_t* mask, void* hip_stream);
+
+/* Hand-over to the next step without a host round trip (Sec. 3.1: the base model is stage 0 of
+ * the draft): the next draft starts from the base model's state vector at the last position
+ * whose prediction was kept and from the token predicted there (the bonus token).
+ *   hidden      dev [batch, B, n_predict+1, emb_dim] hidden_dtype: base-model states of the
+ *               verified positions, aligned with base_logits of spec_verify
+ *   best_cand, accept_len, out_tokens: outputs of spec_verify (dev)
+ *   next_state  dev [batch, emb_dim] hidden_dtype  = hidden[q, best_cand[q], accept_len[q], :]
+ *   next_tok    dev [batch] int32                  = out_tokens[q, accept_len[q]]
+ * next_state / next_tok can be passed to the next spec_draft on the same stream. */
+spec_status_t spec_advance(const void* hidden, int32_t hidden_dtype, int32_t batch, int32_t B, int32_t n_predict,
+                           int32_t emb_dim, const int32_t* best_cand, const int32_t* accept_len,
+                           const int32_t* out_tokens, void* next_state, int32_t* next_tok, void* hip_stream);
+
 /* Optional launch mode of spec_draft, OFF by default.  When enabled and every stage of a
  * call has at most 16 rows (batch 1 with the paper's trees) and the model is SPEC_BF16 with
  * emb_dim == inner_dim in {512, 1024, 2048, 3072, 4096}, spec_draft runs the whole draft

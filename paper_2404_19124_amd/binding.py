@@ -22,7 +22,7 @@ SPEC_OK, SPEC_EINVAL, SPEC_ESHAPE, SPEC_EDTYPE, SPEC_ENOMEM, SPEC_EHIP = 0, -1, 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecdraft.so")
 
 EXPORTS = ["spec_create", "spec_destroy", "spec_draft", "spec_verify", "spec_head_logp", "spec_model_scalars",
-           "spec_profile_enable", "spec_profile_read", "spec_copy_probe", "spec_set_fused", "spec_fused_phase_us", "spec_last_error", "spec_version"]
+           "spec_profile_enable", "spec_profile_read", "spec_copy_probe", "spec_set_fused", "spec_fused_phase_us", "spec_tree_metadata", "spec_advance", "spec_last_error", "spec_version"]
 
 
 class SpecError(RuntimeError):
@@ -86,6 +86,10 @@ def lib() -> C.CDLL:
         l.spec_set_fused.argtypes = [C.c_void_p, C.c_int32]
         l.spec_fused_phase_us.restype = C.c_int
         l.spec_fused_phase_us.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)]
+        l.spec_tree_metadata.restype = C.c_int
+        l.spec_tree_metadata.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 7
+        l.spec_advance.restype = C.c_int
+        l.spec_advance.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 6
         l.spec_copy_probe.restype = C.c_int
         l.spec_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         l.spec_last_error.restype = C.c_char_p
@@ -224,6 +228,23 @@ def spec_fused_phase_us(model: SpecModel):
     n = C.c_int32()
     _check(lib().spec_fused_phase_us(model.handle, buf, 32, C.byref(n)))
     return [float(x) for x in buf[:n.value]]
+
+
+def spec_tree_metadata(cand_tokens: torch.Tensor, node_tok: torch.Tensor, node_parent: torch.Tensor,
+                       node_depth: torch.Tensor, n_nodes: torch.Tensor, cand_node: torch.Tensor,
+                       mask: Optional[torch.Tensor] = None, stream=None) -> None:
+    b, Bc, n = cand_tokens.shape
+    _check(lib().spec_tree_metadata(_ptr(cand_tokens), b, Bc, n, _ptr(node_tok), _ptr(node_parent), _ptr(node_depth),
+                                    _ptr(n_nodes), _ptr(cand_node), _ptr(mask) if mask is not None else None,
+                                    _stream_ptr(stream)))
+
+
+def spec_advance(hidden: torch.Tensor, best_cand: torch.Tensor, accept_len: torch.Tensor, out_tokens: torch.Tensor,
+                 next_state: torch.Tensor, next_tok: torch.Tensor, stream=None) -> None:
+    b, Bc, n1, E = hidden.shape
+    dtype = {torch.float32: SPEC_F32, torch.bfloat16: SPEC_BF16}[hidden.dtype]
+    _check(lib().spec_advance(_ptr(hidden), dtype, b, Bc, n1 - 1, E, _ptr(best_cand), _ptr(accept_len),
+                              _ptr(out_tokens), _ptr(next_state), _ptr(next_tok), _stream_ptr(stream)))
 
 
 def spec_copy_probe(src: torch.Tensor, dst: torch.Tensor, stream=None) -> int:

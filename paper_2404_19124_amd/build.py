@@ -26,6 +26,7 @@ SOURCES = [
     "kernels_head_skinny.hip",
     "kernels_head_gemm.hip",
     "kernels_draft_fused.hip",
+    "kernels_tree_meta.hip",
 ]
 
 FLAGS = [

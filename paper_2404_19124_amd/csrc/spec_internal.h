@@ -168,4 +168,12 @@ hipError_t launch_accept(const int32_t* greedy, const int32_t* cand, int batch, 
                          int32_t* best_cand, int32_t* out_tokens, int32_t* n_out, int32_t* accept_all,
                          hipStream_t st);
 
+// ---- token tree of the candidates, hand-over to the next step ----------------
+constexpr int kMaxTreeItems = 4096;  // B * n_predict per sequence (3 ints of LDS each)
+hipError_t launch_tree_meta(const int32_t* cand, int batch, int B, int n, int32_t* node_tok, int32_t* node_parent,
+                            int32_t* node_depth, int32_t* n_nodes, int32_t* cand_node, uint8_t* mask, hipStream_t st);
+hipError_t launch_advance(const void* hidden, int64_t row_bytes, int batch, int B, int n, const int32_t* best,
+                          const int32_t* accept, const int32_t* out_tokens, void* next_state, int32_t* next_tok,
+                          hipStream_t st);
+
 }  // namespace specdraft

@@ -664,6 +664,38 @@ extern "C" spec_status_t spec_verify(const void* base_logits, int32_t logits_dty
   return SPEC_OK;
 }
 
+extern "C" spec_status_t spec_tree_metadata(const int32_t* cand_tokens, int32_t batch, int32_t B, int32_t n_predict,
+                                            int32_t* node_tok, int32_t* node_parent, int32_t* node_depth,
+                                            int32_t* n_nodes, int32_t* cand_node, uint8_t* mask, void* hip_stream) {
+  if (!cand_tokens || !node_tok || !node_parent || !node_depth || !n_nodes || !cand_node)
+    return fail(SPEC_EINVAL, "a required pointer is NULL");
+  if (batch < 1 || B < 1) return fail(SPEC_EINVAL, "batch and B must be >= 1");
+  if (n_predict < 1 || n_predict > SPEC_MAX_STAGES)
+    return fail(SPEC_EINVAL, "n_predict = %d outside [1, %d]", n_predict, SPEC_MAX_STAGES);
+  if ((int64_t)B * n_predict > kMaxTreeItems)
+    return fail(SPEC_ESHAPE, "B * n_predict = %lld exceeds %d", (long long)B * n_predict, kMaxTreeItems);
+  HIP_TRY(launch_tree_meta(cand_tokens, batch, B, n_predict, node_tok, node_parent, node_depth, n_nodes, cand_node, mask,
+                           static_cast<hipStream_t>(hip_stream)));
+  return SPEC_OK;
+}
+
+extern "C" spec_status_t spec_advance(const void* hidden, int32_t hidden_dtype, int32_t batch, int32_t B,
+                                      int32_t n_predict, int32_t emb_dim, const int32_t* best_cand,
+                                      const int32_t* accept_len, const int32_t* out_tokens, void* next_state,
+                                      int32_t* next_tok, void* hip_stream) {
+  if (!hidden || !best_cand || !accept_len || !out_tokens || !next_state || !next_tok)
+    return fail(SPEC_EINVAL, "a required pointer is NULL");
+  if (hidden_dtype != SPEC_F32 && hidden_dtype != SPEC_BF16)
+    return fail(SPEC_EDTYPE, "hidden_dtype = %d is neither SPEC_F32 nor SPEC_BF16", hidden_dtype);
+  if (batch < 1 || B < 1 || emb_dim < 1) return fail(SPEC_EINVAL, "batch, B and emb_dim must be >= 1");
+  if (n_predict < 1 || n_predict > SPEC_MAX_STAGES)
+    return fail(SPEC_EINVAL, "n_predict = %d outside [1, %d]", n_predict, SPEC_MAX_STAGES);
+  const int64_t row_bytes = (int64_t)emb_dim * (hidden_dtype == SPEC_BF16 ? 2 : 4);
+  HIP_TRY(launch_advance(hidden, row_bytes, batch, B, n_predict, best_cand, accept_len, out_tokens, next_state, next_tok,
+                         static_cast<hipStream_t>(hip_stream)));
+  return SPEC_OK;
+}
+
 extern "C" const char* spec_last_error(void) { return g_err; }
 
 extern "C" spec_status_t spec_version(int32_t* major, int32_t* minor) {
