@@ -71,23 +71,12 @@ GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
   else if (R <= 64 && (int64_t)n_head + n_proj >= (int64_t)128 * (n_cu > 0 ? n_cu : 256)) {
     pl.mi = 4; pl.ni = 4; pl.kcap = 8;
   }
-  else if (R <= 64 || k_top > 4) { pl.mi = 4; pl.ni = 1; pl.kcap = 8; }
+  else if (R <= 64) { pl.mi = 4; pl.ni = 1; pl.kcap = 8; }
   else {
-    // state-row block of 96 or 128 rows: the one whose busiest workgroup does the least
-    // matrix-core work (tiles of its range x rows of its block)
+    // wide kernel, 96-row state blocks; the per-lane top-k lists are as short as k_top allows
+    pl.mi = 6;
     pl.ni = 4;
-    pl.kcap = k_top <= 2 ? 2 : 4;
-    int64_t best_cost = -1;
-    int best = 8;
-    for (int mi : {6}) {
-      GemmPlan c = pl;
-      c.mi = mi;
-      fill_plan(c, R, n_head, n_proj, n_cu);
-      const int total = (n_head + 255) / 256 + (n_proj + 255) / 256;
-      const int64_t cost = (int64_t)((total + c.n_ranges - 1) / c.n_ranges) * mi;
-      if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = mi; }
-    }
-    pl.mi = best;
+    pl.kcap = k_top <= 2 ? 2 : (k_top <= 4 ? 4 : 8);
   }
   fill_plan(pl, R, n_head, n_proj, n_cu);
   return pl;
@@ -838,6 +827,7 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
     case 4 * 100 + 4 * 10 + 8: return launch_gemm32_t<2, 2, 8>(a, st, ev_start, ev_stop);
     case 6 * 100 + 4 * 10 + 2: return launch_gemm32_t<3, 2, 2>(a, st, ev_start, ev_stop);
     case 6 * 100 + 4 * 10 + 4: return launch_gemm32_t<3, 2, 4>(a, st, ev_start, ev_stop);
+    case 6 * 100 + 4 * 10 + 8: return launch_gemm32_t<3, 2, 8>(a, st, ev_start, ev_stop);
     default: return hipErrorInvalidValue;
   }
 }
