@@ -34,13 +34,15 @@ hipError_t launch_stage(const StageJob& job, hipStream_t st) {
 // every leaf by the sum of its tokens' log-probabilities (added in stage order),
 // keep the B best.  One workgroup per sequence.
 // ---------------------------------------------------------------------------
-// 512 threads: eight waves merge eight rows at a time, and each wave may use 256 registers (the
-// widest merge needs more than the 128 a 1024-thread workgroup would leave it).
-__global__ __launch_bounds__(512) void tree_kernel(TreeJob j) {
+// NT = 512: eight waves merge eight rows at a time and each wave may use 256 registers (the
+// widest merges need more than the 128 a 1024-thread workgroup would leave).  NT = 1024 for
+// last-stage top-k <= 4 (KWAVE = 4): sixteen rows per pass, one pass for the paper's trees.
+template <int NT, int KWAVE>
+__global__ __launch_bounds__(NT) void tree_kernel(TreeJob j) {
   __shared__ float sc[kMaxLeaves];
   __shared__ int s_k[kMaxStages];
   __shared__ int64_t s_off[kMaxStages];
-  __shared__ float merge_lds[64];
+  __shared__ float merge_lds[32 * (NT / 256)];
   TreeArgs a;
   a.n = j.n; a.B = j.B; a.L = j.L; a.nparts = j.nparts;
   a.k_last = 1; a.off_last = 0; a.row_off_last = 0;
@@ -52,11 +54,16 @@ __global__ __launch_bounds__(512) void tree_kernel(TreeJob j) {
   a.part = j.part; a.tok = j.tok; a.logp = j.logp; a.lse = j.lse;
   a.cand_tokens = j.cand_tokens; a.cand_scores = j.cand_scores; a.cand_leaf = j.cand_leaf;
   __syncthreads();
-  tree_body<512, kMaxTopK>(a, blockIdx.x, s_k, s_off, sc, merge_lds);
+  tree_body<NT, KWAVE>(a, blockIdx.x, s_k, s_off, sc, merge_lds);
 }
 
 hipError_t launch_tree(const TreeJob& job, hipStream_t st) {
-  hipLaunchKernelGGL(tree_kernel, dim3(job.batch), dim3(512), 0, st, job);
+  const int k_last = job.top_k[job.n - 1];
+  const int rows_last = job.L / k_last;
+  if (k_last <= 4 && rows_last > 8)
+    hipLaunchKernelGGL((tree_kernel<1024, 4>), dim3(job.batch), dim3(1024), 0, st, job);
+  else
+    hipLaunchKernelGGL((tree_kernel<512, kMaxTopK>), dim3(job.batch), dim3(512), 0, st, job);
   return hipGetLastError();
 }
 
