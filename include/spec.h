@@ -219,6 +219,11 @@ spec_status_t spec_advance(const void* hidden, int32_t hidden_dtype, int32_t bat
  * candidates of the failed call are invalid) and the mode switches itself off. */
 spec_status_t spec_set_fused(spec_model_t* m, int32_t enable);
 
+/* Bound of one wait at the fused launch's device-wide barrier (default 2 s).  With 0 a workgroup
+ * that finds a barrier not yet complete gives up at once: every workgroup then leaves the kernel
+ * normally, which exercises the failure handling described above without hanging anything. */
+spec_status_t spec_fused_timeout(spec_model_t* m, int64_t microseconds);
+
 /* Durations, in microseconds, between the phase boundaries of the model's last fused
  * draft launch as seen by its first workgroup: [proj_1][barrier][stage_1 + barrier + head_1]
  * [barrier][stage_2 + barrier + head_2] ... [barrier][tree].  Synchronises with the device

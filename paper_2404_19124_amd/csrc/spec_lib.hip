@@ -81,6 +81,7 @@ struct spec_model {
   unsigned long long* clocks = nullptr;
   int clocks_n = 0;
   bool fused_enabled = false;  // opt-in (spec_set_fused): measured slower than separate launches
+  unsigned long long fused_timeout_ticks = 200000000ull;  // 2 s of the 100 MHz wall clock
   // Workspace of the whole-draft kernel, one set PER STAGE: inside one launch a buffer
   // that other workgroups read is written once and never read before that, so no cache
   // can hold a stale line of it (see kernels_draft_fused.hip)
@@ -373,6 +374,13 @@ extern "C" spec_status_t spec_set_fused(spec_model_t* m, int32_t enable) {
   return SPEC_OK;
 }
 
+extern "C" spec_status_t spec_fused_timeout(spec_model_t* m, int64_t microseconds) {
+  if (!m) return fail(SPEC_EINVAL, "model is NULL");
+  if (microseconds < 0 || microseconds > 60000000) return fail(SPEC_EINVAL, "microseconds outside [0, 60 s]");
+  m->fused_timeout_ticks = (unsigned long long)microseconds * 100ull;
+  return SPEC_OK;
+}
+
 extern "C" spec_status_t spec_fused_phase_us(spec_model_t* m, float* us, int32_t cap, int32_t* n) {
   if (!m || !us || !n) return fail(SPEC_EINVAL, "a required pointer is NULL");
   unsigned long long t[2 * kMaxStages + 4] = {0};
@@ -484,6 +492,9 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
     // invalid, and the arrival counter is in an unknown state
     *m->fail_host = 0;
     m->fused_enabled = false;
+    // (the counters restart from zero, should the caller switch the mode on again)
+    m->barrier_value = 0;
+    (void)hipMemsetAsync(m->barrier, 0, fused_barrier_bytes(), st);
     return fail(SPEC_EHIP, "an earlier fused draft launch timed out at its device-wide barrier (workgroups not "
                            "co-resident); its results are invalid; further drafts use separate launches");
   }
@@ -556,7 +567,7 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
     fj.barrier = m->barrier;
     fj.fail_flag = m->fail_dev;
     fj.clocks = m->clocks;
-    fj.timeout_ticks = 200000000ull;  // 2 s of the 100 MHz wall clock
+    fj.timeout_ticks = m->fused_timeout_ticks;
     fj.head[0] = make_head_job(m, -1, 0, state, true, E, batch, 0, nullptr, m->fpz[0]);
     fj.head[0].nparts = grid;
     int64_t sum_rows = batch;

@@ -119,6 +119,37 @@ def test_fused_draft_matches_oracle_and_separate_launches(case):
     assert torch.equal(step_f.cand_tokens, step_s.cand_tokens)
 
 
+def test_fused_draft_barrier_timeout_is_reported_and_the_model_recovers():
+    """A barrier wait bound of zero makes the fused launch give up (all workgroups leave
+    normally); the next draft reports it, the mode switches off and later drafts are right."""
+    wl = W.Workload("fused_timeout", 512, 512, 1000, 3, (5, 3, 2), 10, 1, "bf16", "f32", 0.6, seed=17, emb_std=0.3)
+    rep, step, od, _ = run_workload(wl, ln_affine="random", gen_device="cpu", fused=False)
+    good = step.cand_tokens.clone()
+    gen = W.make_generator(wl.seed, "cpu")
+    W.make_speculator(wl, gen, device="cpu", ln_affine="random")
+    state, last = W.make_draft_inputs(wl, gen, device="cpu")
+    state, last = state.cuda(), last.cuda()
+    B.spec_set_fused(step.model, True)
+    B.spec_fused_timeout(step.model, 0)
+    step.draft(state, last)            # gives up at its first incomplete barrier
+    torch.cuda.synchronize()
+    with pytest.raises(B.SpecError) as err:
+        step.draft(state, last)
+    assert "barrier" in str(err.value)
+    step.cand_tokens.zero_()
+    step.draft(state, last)            # separate launches from now on
+    torch.cuda.synchronize()
+    assert torch.equal(step.cand_tokens, good)
+    B.spec_fused_timeout(step.model, 2000000)
+    B.spec_set_fused(step.model, True)  # switched on again: the barrier restarts from zero
+    step.cand_tokens.zero_()
+    step.draft(state, last)
+    step.draft(state, last)
+    torch.cuda.synchronize()
+    assert torch.equal(step.cand_tokens, good)
+    assert len(B.spec_fused_phase_us(step.model)) == 2 * wl.n_predict + 3
+
+
 SMALL_F32 = [
     ("f32_b1", 256, 256, 1024, 3, (4, 3, 2), 24, 1),
     ("f32_b5", 100, 72, 333, 3, (3, 3, 2), 7, 5),           # nothing a multiple of the tile sizes
