@@ -24,16 +24,27 @@ __global__ __launch_bounds__(1024) void argmax_rows_kernel(const void* logits, i
     if (VEC) {
       // (non-temporal: the logits are read once; a stream that does not allocate in the
       // caches is the faster one on this chip)
+      // eight loads in flight per thread: at small batch the kernel is a chain of memory
+      // round trips, not a stream
       const u32x4* xv = reinterpret_cast<const u32x4*>(x);
-      for (int c = tid; c < V / 8; c += 1024) {
-        const u32x4 raw = __builtin_nontemporal_load(xv + c);
-        const uint32_t w[4] = {raw[0], raw[1], raw[2], raw[3]};
+      const int nvec = V / 8;
+      constexpr int U = 8;
+      for (int c0 = tid; c0 < nvec; c0 += 1024 * U) {
+        u32x4 raw[U];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const float lo = bf16_bits_to_f32(w[q] & 0xffffu), hi = bf16_bits_to_f32(w[q] >> 16);
-          const int i0 = c * 8 + 2 * q;
-          if (before(lo, i0, bv, bi)) { bv = lo; bi = i0; }
-          if (before(hi, i0 + 1, bv, bi)) { bv = hi; bi = i0 + 1; }
+        for (int u = 0; u < U; ++u) raw[u] = __builtin_nontemporal_load(xv + min(c0 + u * 1024, nvec - 1));
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int c = c0 + u * 1024;
+          if (c < nvec) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const float lo = bf16_bits_to_f32(raw[u][q] & 0xffffu), hi = bf16_bits_to_f32(raw[u][q] >> 16);
+              const int i0 = c * 8 + 2 * q;
+              if (before(lo, i0, bv, bi)) { bv = lo; bi = i0; }
+              if (before(hi, i0 + 1, bv, bi)) { bv = hi; bi = i0 + 1; }
+            }
+          }
         }
       }
       for (int i = (V / 8) * 8 + tid; i < V; i += 1024) {
@@ -50,12 +61,21 @@ __global__ __launch_bounds__(1024) void argmax_rows_kernel(const void* logits, i
     const float* x = static_cast<const float*>(logits) + row * V;
     if (VEC) {
       const f32x4* xv = reinterpret_cast<const f32x4*>(x);
-      for (int c = tid; c < V / 4; c += 1024) {
-        const f32x4 r = __builtin_nontemporal_load(xv + c);
-        const float v[4] = {r[0], r[1], r[2], r[3]};
+      const int nvec = V / 4;
+      constexpr int U = 8;
+      for (int c0 = tid; c0 < nvec; c0 += 1024 * U) {
+        f32x4 r[U];
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          if (before(v[q], c * 4 + q, bv, bi)) { bv = v[q]; bi = c * 4 + q; }
+        for (int u = 0; u < U; ++u) r[u] = __builtin_nontemporal_load(xv + min(c0 + u * 1024, nvec - 1));
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int c = c0 + u * 1024;
+          if (c < nvec) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+              if (before(r[u][q], c * 4 + q, bv, bi)) { bv = r[u][q]; bi = c * 4 + q; }
+          }
+        }
       }
       for (int i = (V / 4) * 4 + tid; i < V; i += 1024) {
         const float v = x[i];
