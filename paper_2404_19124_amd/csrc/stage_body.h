@@ -123,7 +123,7 @@ __device__ __forceinline__ void stage_row(const StageJob& j, int r, float* lds) 
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
         const float y = (z[ci][q] - mean) * rstd * ga[ci][q] + be[ci][q];
-        s[q] = 0.5f * y * (1.0f + erff(y * 0.70710678118654752440f));
+        s[q] = 0.5f * y * (1.0f + erf_as(y * 0.70710678118654752440f));
       }
       if (BF16) {
         uint4 o;
