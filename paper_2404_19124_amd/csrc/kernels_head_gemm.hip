@@ -71,7 +71,14 @@ GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
   else if (R <= 64 && (int64_t)n_head + n_proj >= (int64_t)128 * (n_cu > 0 ? n_cu : 256)) {
     pl.mi = 4; pl.ni = 4; pl.kcap = 8;
   }
-  else if (R <= 64) { pl.mi = 4; pl.ni = 1; pl.kcap = 8; }
+  else if (R <= 64) {
+    // a short weight matrix (a projection alone) has too few 64-row tiles to fill the chip with
+    // 64-row state blocks: two 32-row blocks double the workgroups (the second reads the weights from L2)
+    const int64_t tiles = ((int64_t)n_head + 63) / 64 + ((int64_t)n_proj + 63) / 64;
+    pl.mi = tiles < (n_cu > 0 ? n_cu : 256) ? 2 : 4;
+    pl.ni = 1;
+    pl.kcap = 8;
+  }
   else {
     // wide kernel, 96-row state blocks; the per-lane top-k lists are as short as k_top allows
     pl.mi = 6;
