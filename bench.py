@@ -34,7 +34,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
 # weight-row blocks per wave, capacity of the per-lane top-k lists)
 KERNEL_NAMES = {0: "head_skinny_kernel", 1: "head_gemm_kernel<2,1,8>",
                 2: "head_gemm_kernel<4,1,8> | head_gemm32_kernel<2,2,8>", 3: "head_gemm32_kernel<3,2,*>",
-                4: "draft_fused_kernel"}
+                4: "draft_fused_kernel", 5: "head_gemm32_kernel<5,2,*>"}
 
 
 def main() -> int:

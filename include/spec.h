@@ -160,7 +160,8 @@ spec_status_t spec_head_logp(spec_model_t* m, int32_t stage, const void* states,
  * every contraction launch (they receive that kernel's begin / end time on the
  * caller's stream); nothing else changes.
  *   kernel: 0 = rows<=16 streaming kernel, 1..3 = dense kernel with 32/64/96-row state blocks,
- *           4 = whole draft in one launch (rows / weight_rows summed over its contractions)
+ *           4 = whole draft in one launch (rows / weight_rows summed over its contractions),
+ *           5 = dense kernel with 160-row state blocks
  *   rows, weight_rows, k: the contraction is [rows, k] x [weight_rows, k]^T
  *                  (weight_rows counts head and fused next-projection rows together)
  *   ms: elapsed time between the two events */

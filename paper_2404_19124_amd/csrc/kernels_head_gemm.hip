@@ -47,6 +47,11 @@ constexpr int NSET = PD + 1;
 constexpr int GD = 4;
 static_assert(GD <= NSET, "a state register set is reused NSET slabs later");
 
+#ifndef SPEC_TALL_COST
+#define SPEC_TALL_COST 1.35
+#endif
+constexpr double kTallSlabCost = SPEC_TALL_COST;
+
 static void fill_plan(GemmPlan& pl, int R, int n_head, int n_proj, int n_cu) {
   pl.m_tiles = (R + 16 * pl.mi - 1) / (16 * pl.mi);
   const int nt_head = (n_head + 64 * pl.ni - 1) / (64 * pl.ni);
@@ -80,10 +85,23 @@ GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
     pl.kcap = 8;
   }
   else {
-    // wide kernel, 96-row state blocks; the per-lane top-k lists are as short as k_top allows
-    pl.mi = 6;
+    // wide kernel; the per-lane top-k lists are as short as k_top allows
     pl.ni = 4;
     pl.kcap = k_top <= 2 ? 2 : (k_top <= 4 ? 4 : 8);
+    pl.mi = 6;
+    fill_plan(pl, R, n_head, n_proj, n_cu);
+    if (pl.kcap <= 4) {
+      // 96- or 160-row state blocks: the longest range decides the launch, a K slab of the
+      // taller block costs ~1.35x the shorter one's (more matrix work per byte from L2)
+      GemmPlan tall = pl;
+      tall.mi = 10;
+      fill_plan(tall, R, n_head, n_proj, n_cu);
+      const int total = (n_head + 255) / 256 + (n_proj + 255) / 256;
+      const double c96 = 1.0 * ((total + pl.n_ranges - 1) / pl.n_ranges);
+      const double c160 = kTallSlabCost * ((total + tall.n_ranges - 1) / tall.n_ranges);
+      if (c160 < c96) pl = tall;
+    }
+    return pl;
   }
   fill_plan(pl, R, n_head, n_proj, n_cu);
   return pl;
@@ -432,6 +450,12 @@ __device__ __forceinline__ void interleave_half() {
 template <int MB, int NB, int KT>
 __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
   constexpr int MI = 2 * MB, NI = 2 * NB;  // in 16-row tiles of the layout
+  // the tall block has 1.7x the matrix work per slab: two slabs ahead cover the same latency,
+  // and the registers of the third go to the accumulators
+  constexpr int PD = MB >= 5 ? 2 : ::specdraft::PD;
+  constexpr int NSET = PD + 1;
+  constexpr int GD = MB >= 5 ? 3 : ::specdraft::GD;
+  static_assert(GD <= NSET && NSET >= 3, "register sets / LDS buffers are reused NSET slabs later");
   extern __shared__ __align__(16) unsigned char smem[];
   u32x4* ldsB = reinterpret_cast<u32x4*>(smem);  // [NSET][MI*KS*64]
   constexpr int SLAB = MI * KS * 64;             // slots per slab
@@ -836,6 +860,8 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
     case 6 * 100 + 4 * 10 + 2: return launch_gemm32_t<3, 2, 2>(a, st, ev_start, ev_stop);
     case 6 * 100 + 4 * 10 + 4: return launch_gemm32_t<3, 2, 4>(a, st, ev_start, ev_stop);
     case 6 * 100 + 4 * 10 + 8: return launch_gemm32_t<3, 2, 8>(a, st, ev_start, ev_stop);
+    case 10 * 100 + 4 * 10 + 2: return launch_gemm32_t<5, 2, 2>(a, st, ev_start, ev_stop);
+    case 10 * 100 + 4 * 10 + 4: return launch_gemm32_t<5, 2, 4>(a, st, ev_start, ev_stop);
     default: return hipErrorInvalidValue;
   }
 }
