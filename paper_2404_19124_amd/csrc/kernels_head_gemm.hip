@@ -52,10 +52,13 @@ static_assert(GD <= NSET, "a state register set is reused NSET slabs later");
 #endif
 constexpr double kTallSlabCost = SPEC_TALL_COST;
 
+// Workgroup tiles of the two weight matrices for tiles of ts 16-row weight tiles.
+static int plan_tiles(int n_rows, int ts) { return ((n_rows + 15) / 16 + ts - 1) / ts; }
+
 static void fill_plan(GemmPlan& pl, int R, int n_head, int n_proj, int n_cu) {
   pl.m_tiles = (R + 16 * pl.mi - 1) / (16 * pl.mi);
-  const int nt_head = (n_head + 64 * pl.ni - 1) / (64 * pl.ni);
-  const int nt_proj = (n_proj + 64 * pl.ni - 1) / (64 * pl.ni);
+  const int nt_head = plan_tiles(n_head, pl.ts);
+  const int nt_proj = plan_tiles(n_proj, pl.ts);
   const int total = nt_head + nt_proj;
   // narrow blocks are bandwidth-bound and light on registers: two workgroups per CU keep more loads in flight
   int nr = (pl.ni == 1 ? 2 : 1) * (n_cu > 0 ? n_cu : 256) / pl.m_tiles;
@@ -68,13 +71,35 @@ static void fill_plan(GemmPlan& pl, int R, int n_head, int n_proj, int n_cu) {
   pl.nparts = np;
 }
 
+// Wide kernel with at most one 256-row tile per range (fewer tiles than CUs: an HBM-bound
+// launch that leaves CUs idle): the smallest tile, in 16-row weight tiles, that still gives every
+// range at most one.  A tile costs its K loop whether all four waves have valid rows or not, but
+// every range then streams fewer weight rows and the idle ranges get one: 157 tiles of 256 rows
+// over 256 CUs become 252 tiles of 160.  (With several tiles per range the launch is bound by
+// the matrix cores or the L2, and more K loops only cost: measured.)
+static void shrink_tile(GemmPlan& pl, int R, int n_head, int n_proj, int n_cu) {
+  const int per16 = (plan_tiles(n_head, 16) + plan_tiles(n_proj, 16) + pl.n_ranges - 1) / pl.n_ranges;
+  if (per16 > 1 || pl.mi > 6) return;
+  for (int ts = 4; ts < 16; ++ts) {
+    GemmPlan c = pl;
+    c.ts = ts;
+    fill_plan(c, R, n_head, n_proj, n_cu);
+    const int per = (plan_tiles(n_head, ts) + plan_tiles(n_proj, ts) + c.n_ranges - 1) / c.n_ranges;
+    if (per <= per16) { pl = c; return; }
+  }
+}
+
 GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
   GemmPlan pl;
+  pl.ts = 4;
   if (R <= 32) { pl.mi = 2; pl.ni = 1; pl.kcap = 8; }
   // 33..64 rows against a long weight matrix (at least one 256-row tile per two CUs): the
   // wide kernel re-reads the states a quarter as often per weight byte as the narrow one
   else if (R <= 64 && (int64_t)n_head + n_proj >= (int64_t)128 * (n_cu > 0 ? n_cu : 256)) {
-    pl.mi = 4; pl.ni = 4; pl.kcap = 8;
+    pl.mi = 4; pl.ni = 4; pl.kcap = 8; pl.ts = 16;
+    fill_plan(pl, R, n_head, n_proj, n_cu);
+    shrink_tile(pl, R, n_head, n_proj, n_cu);
+    return pl;
   }
   else if (R <= 64) {
     // a short weight matrix (a projection alone) has too few 64-row tiles to fill the chip with
@@ -87,6 +112,7 @@ GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
   else {
     // wide kernel; the per-lane top-k lists are as short as k_top allows
     pl.ni = 4;
+    pl.ts = 16;
     pl.kcap = k_top <= 2 ? 2 : (k_top <= 4 ? 4 : 8);
     pl.mi = 6;
     fill_plan(pl, R, n_head, n_proj, n_cu);
@@ -101,6 +127,7 @@ GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
       const double c160 = kTallSlabCost * ((total + tall.n_ranges - 1) / tall.n_ranges);
       if (c160 < c96) pl = tall;
     }
+    shrink_tile(pl, R, n_head, n_proj, n_cu);
     return pl;
   }
   fill_plan(pl, R, n_head, n_proj, n_cu);
@@ -119,6 +146,7 @@ struct GemmArgs {
   const u32x4* b;     // packed states
   int R, mt_total;
   int m_tiles, n_ranges, chunk;  // chunk = workgroups per XCD
+  int ts;                        // 16-row weight tiles per workgroup tile (wide kernel)
   int k_top;
   Partials part;
   int nparts;
@@ -447,7 +475,7 @@ __device__ __forceinline__ void interleave_half() {
 // needs.  A lane then holds, for state row c of block mb, the logits of weight rows
 // 32 nb + 4 h + 8 q + r (accumulator entry 4 q + r), in increasing vocabulary order.
 // MB / NB = 32-row blocks of states per workgroup / of weight rows per wave.
-template <int MB, int NB, int KT>
+template <int MB, int NB, int KT, bool VT>
 __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
   constexpr int MI = 2 * MB, NI = 2 * NB;  // in 16-row tiles of the layout
   // the tall block has 1.7x the matrix work per slab: two slabs ahead cover the same latency,
@@ -488,14 +516,21 @@ __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
   }
 
   // weight fragment pointers of this wave for a given tile of the list
+  // VT (variable tile): a tile holds p.ts <= 4 * NI 16-row weight tiles instead of 4 * NI; wave w
+  // owns tiles [w * NI, (w + 1) * NI) of it.  A 32-row block past the tile's end is masked in the
+  // epilogue; its loads repeat the
+  // tile's last 16 rows (lines another wave of the workgroup requests at the same time: no
+  // extra HBM traffic, and short tiles are only planned where HBM is the bound).
   const u32x4* wptr[NB];
-  auto set_tile = [&](int t, const u32x4* (&wp)[NB], int (&ntv)[NB], int& mat) {
+  auto set_tile = [&](int t, const u32x4* (&wp)[NB], int (&ntv)[NB], int& mat, int& tend) {
     mat = t >= p.n_tiles[0] ? 1 : 0;
     const int ntile = t - (mat ? p.n_tiles[0] : 0);
+    const int ts = VT ? p.ts : 4 * NI;
+    tend = VT ? min((ntile + 1) * ts, p.nt_total[mat]) : p.nt_total[mat];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      ntv[nb] = (ntile * 4 + wave) * NI + 2 * nb;  // first 16-row tile of the block (even)
-      const int ntc = min(ntv[nb] + (c32 >> 4), p.nt_total[mat] - 1);
+      ntv[nb] = ntile * ts + wave * NI + 2 * nb;  // first 16-row tile of the block
+      const int ntc = min(ntv[nb] + (c32 >> 4), tend - 1);
       wp[nb] = p.w[mat] + (int64_t)ntc * kt * 64 + half * 16 + (c32 & 15);
     }
   };
@@ -510,7 +545,11 @@ __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
   auto load_a1 = [&](u32x4 (&aw)[NB][2 * KS], int sl, int nb) {
     const int64_t off = (int64_t)sl * KS * 64;
 #pragma unroll
-    for (int q = 0; q < 2 * KS; ++q) aw[nb][q] = wptr[nb][off + q * 32];  // q = 2 * K-step + sub-step
+    for (int q = 0; q < 2 * KS; ++q) {  // q = 2 * K-step + sub-step
+      // one block of state rows (MB == 2 serves <= 64 rows): nobody shares the weight stream, it need not stay cached
+      if constexpr (MB == 2) aw[nb][q] = __builtin_nontemporal_load(wptr[nb] + off + q * 32);
+      else aw[nb][q] = wptr[nb][off + q * 32];
+    }
   };
   auto load_a = [&](u32x4 (&aw)[NB][2 * KS], int sl) {
 #pragma unroll
@@ -533,8 +572,8 @@ __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
   }
   bool any_head = false;
 
-  int nt[NB], mat = 0;
-  set_tile(t0, wptr, nt, mat);
+  int nt[NB], mat = 0, tend = 0;
+  set_tile(t0, wptr, nt, mat, tend);
 #pragma unroll
   for (int q = 0; q < GD; ++q)
     if (q < nslab) load_g(g[q], q);
@@ -629,12 +668,12 @@ __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
     }
 
     // ---- the next tile's first slabs are requested before the epilogue runs
-    const int cur_mat = mat;
+    const int cur_mat = mat, cur_end = tend;
     int cur_nt[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) cur_nt[nb] = nt[nb];
     if (t + 1 < t1) {
-      set_tile(t + 1, wptr, nt, mat);
+      set_tile(t + 1, wptr, nt, mat, tend);
 #pragma unroll
       for (int q = 0; q < GD; ++q)
         if (q < nslab) load_g(g[q], q);
@@ -644,7 +683,8 @@ __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
     }
 
     // ---- epilogue of tile t
-    const int n_valid = p.n_valid[cur_mat];
+    // (variable tile: rows past the tile's end are another tile's)
+    const int n_valid = VT ? min(p.n_valid[cur_mat], cur_end * 16) : p.n_valid[cur_mat];
     if (cur_mat == 1 || p.mode0 == 1) {
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
@@ -668,7 +708,10 @@ __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
       }
     } else {
       any_head = true;
-      // only the tile that holds the end of the vocabulary needs the validity mask
+    }
+    // (a wave whose rows all lie past the tile's end has nothing to add)
+    if (cur_mat == 0 && p.mode0 == 0 && (!VT || cur_nt[0] < cur_end)) {
+      // only a block that reaches past the end of the tile or of the vocabulary needs the validity mask
       const bool edge = (cur_nt[NB - 1] + 2) * 16 > n_valid;
       constexpr float kLog2e = 1.4426950408889634f;
 #pragma unroll
@@ -800,17 +843,17 @@ static hipError_t launch_gemm_t(const GemmArgs& a, hipStream_t st, hipEvent_t ev
   return hipGetLastError();
 }
 
-template <int MB, int NB, int KT>
+template <int MB, int NB, int KT, bool VT>
 static hipError_t launch_gemm32_t(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const size_t smem = gemm_smem(2 * MB, KT);
   static bool attr_set = false;  // per instantiation
   if (!attr_set && smem > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_gemm32_kernel<MB, NB, KT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_gemm32_kernel<MB, NB, KT, VT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipExtLaunchKernelGGL((head_gemm32_kernel<MB, NB, KT>), dim3(a.chunk * 8), dim3(256), smem, st, ev_start, ev_stop, 0,
+  hipExtLaunchKernelGGL((head_gemm32_kernel<MB, NB, KT, VT>), dim3(a.chunk * 8), dim3(256), smem, st, ev_start, ev_stop, 0,
                         a);
   return hipGetLastError();
 }
@@ -824,7 +867,7 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
     a.w[nm] = static_cast<const u32x4*>(job.w_head);
     a.nt_total[nm] = job.vt_head;
     a.n_valid[nm] = job.n_head;
-    a.n_tiles[nm] = (job.n_head + 64 * pl.ni - 1) / (64 * pl.ni);
+    a.n_tiles[nm] = plan_tiles(job.n_head, pl.ts);
     a.out[nm] = job.out_head;
     a.ldo[nm] = job.ld_head;
     a.mode0 = job.out_head ? 1 : 0;
@@ -835,7 +878,7 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
     a.w[nm] = static_cast<const u32x4*>(job.w_proj);
     a.nt_total[nm] = job.vt_proj;
     a.n_valid[nm] = job.n_proj;
-    a.n_tiles[nm] = (job.n_proj + 64 * pl.ni - 1) / (64 * pl.ni);
+    a.n_tiles[nm] = plan_tiles(job.n_proj, pl.ts);
     a.out[nm] = job.out_proj;
     a.ldo[nm] = job.ld_proj;
     ++nm;
@@ -847,21 +890,29 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
   a.mt_total = (job.R + 15) / 16;
   a.m_tiles = pl.m_tiles;
   a.n_ranges = pl.n_ranges;
+  a.ts = pl.ts;
   a.chunk = (pl.m_tiles * pl.n_ranges + 7) / 8;
   a.k_top = job.k_top;
   a.part = job.part;
   a.nparts = job.nparts;
   if (a.mode0 == 0 && job.k_top > pl.kcap) return hipErrorInvalidValue;
   const int key = pl.mi * 100 + pl.ni * 10 + pl.kcap;
+  const bool vt = pl.ni == 4 && pl.ts != 16;  // wide kernel with short tiles
   switch (key) {
     case 2 * 100 + 1 * 10 + 8: return launch_gemm_t<2, 1, 8>(a, st, ev_start, ev_stop);
     case 4 * 100 + 1 * 10 + 8: return launch_gemm_t<4, 1, 8>(a, st, ev_start, ev_stop);
-    case 4 * 100 + 4 * 10 + 8: return launch_gemm32_t<2, 2, 8>(a, st, ev_start, ev_stop);
-    case 6 * 100 + 4 * 10 + 2: return launch_gemm32_t<3, 2, 2>(a, st, ev_start, ev_stop);
-    case 6 * 100 + 4 * 10 + 4: return launch_gemm32_t<3, 2, 4>(a, st, ev_start, ev_stop);
-    case 6 * 100 + 4 * 10 + 8: return launch_gemm32_t<3, 2, 8>(a, st, ev_start, ev_stop);
-    case 10 * 100 + 4 * 10 + 2: return launch_gemm32_t<5, 2, 2>(a, st, ev_start, ev_stop);
-    case 10 * 100 + 4 * 10 + 4: return launch_gemm32_t<5, 2, 4>(a, st, ev_start, ev_stop);
+    case 4 * 100 + 4 * 10 + 8: return launch_gemm32_t<2, 2, 8, true>(a, st, ev_start, ev_stop);
+    case 6 * 100 + 4 * 10 + 2:
+      return vt ? launch_gemm32_t<3, 2, 2, true>(a, st, ev_start, ev_stop)
+                : launch_gemm32_t<3, 2, 2, false>(a, st, ev_start, ev_stop);
+    case 6 * 100 + 4 * 10 + 4:
+      return vt ? launch_gemm32_t<3, 2, 4, true>(a, st, ev_start, ev_stop)
+                : launch_gemm32_t<3, 2, 4, false>(a, st, ev_start, ev_stop);
+    case 6 * 100 + 4 * 10 + 8:
+      return vt ? launch_gemm32_t<3, 2, 8, true>(a, st, ev_start, ev_stop)
+                : launch_gemm32_t<3, 2, 8, false>(a, st, ev_start, ev_stop);
+    case 10 * 100 + 4 * 10 + 2: return vt ? hipErrorInvalidValue : launch_gemm32_t<5, 2, 2, false>(a, st, ev_start, ev_stop);
+    case 10 * 100 + 4 * 10 + 4: return vt ? hipErrorInvalidValue : launch_gemm32_t<5, 2, 4, false>(a, st, ev_start, ev_stop);
     default: return hipErrorInvalidValue;
   }
 }

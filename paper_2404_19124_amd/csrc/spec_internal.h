@@ -80,6 +80,7 @@ hipError_t launch_head_skinny(const HeadJob& job, int n_cu, hipStream_t st, hipE
 // the projection (store) in one launch.
 struct GemmPlan {
   int mi, ni;        // fragments per wave in M (state rows) and N (weight rows)
+  int ts;            // 16-row weight tiles per workgroup tile (<= 4 * ni; fewer = some waves' rows masked)
   int kcap;          // capacity of the per-lane top-k lists (>= k_top)
   int m_tiles;       // blocks of state rows
   int n_ranges;      // ranges of weight-row tiles
