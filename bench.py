@@ -30,11 +30,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
-# labels of spec_launch_record_t.kernel (template arguments: state-row blocks per workgroup,
-# weight-row blocks per wave, capacity of the per-lane top-k lists)
-KERNEL_NAMES = {0: "head_skinny_kernel", 1: "head_gemm_kernel<2,1,8>",
-                2: "head_gemm_kernel<4,1,8> | head_gemm32_kernel<2,2,8>", 3: "head_gemm32_kernel<3,2,*>",
-                4: "draft_fused_kernel", 5: "head_gemm32_kernel<5,2,*>"}
+# labels of spec_launch_record_t.kernel: the kernel instances as rocprofv3 names them
+def kernel_name(kid: int) -> str:
+    if kid >= 1000:
+        mb, rest = divmod(kid - 1000, 100)
+        return "head_gemm32_kernel<%d, 2, %d, %s>" % (mb, rest // 2, "true" if rest % 2 else "false")
+    return {0: "head_skinny_kernel", 1: "head_gemm_kernel<2, 1, 8>", 2: "head_gemm_kernel<4, 1, 8>",
+            4: "draft_fused_kernel"}[kid]
 
 
 def main() -> int:
@@ -136,7 +138,7 @@ def main() -> int:
         for (kern, rows, wrows, kk), (ms, cnt) in sorted(groups.items()):
             us = ms / cnt * 1e3
             print("  %-24s rows %5d x weights %6d x k %5d : %8.2f us  %7.1f GB/s  %7.1f TFLOP/s  (%d launches)"
-                  % (KERNEL_NAMES[kern], rows, wrows, kk, us, (2.0 * wrows * kk + 2.0 * rows * kk) / us / 1e3,
+                  % (kernel_name(kern), rows, wrows, kk, us, (2.0 * wrows * kk + 2.0 * rows * kk) / us / 1e3,
                      2.0 * rows * wrows * kk / us / 1e6, cnt), file=sys.stderr)
     dom = max(by_kernel, key=lambda k: by_kernel[k]["ms"])
     d = by_kernel[dom]
@@ -146,14 +148,14 @@ def main() -> int:
     # which roof binds this kernel: compare the two ideal times
     t_hbm = d["bytes"] / d["n"] / (HBM_PEAK_GBS * 1e9)
     t_mfma = d["flops"] / d["n"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
-    traffic = _traffic_from_profiles(args.workload, KERNEL_NAMES[dom])
+    traffic = _traffic_from_profiles(args.workload, kernel_name(dom))
     if t_hbm >= t_mfma:
         roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic}
     else:
         roofline = {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic}
-    roofline.update({"kernel": KERNEL_NAMES[dom], "avg_launch_us": round(avg_ms * 1e3, 2),
+    roofline.update({"kernel": kernel_name(dom), "avg_launch_us": round(avg_ms * 1e3, 2),
                      "launches_per_step": d["n"] / args.steps,
                      "algorithmic_bytes_per_launch": d["bytes"] / d["n"],
                      "flops_per_launch": d["flops"] / d["n"],

@@ -159,9 +159,11 @@ spec_status_t spec_head_logp(spec_model_t* m, int32_t stage, const void* states,
  * roofline reports.  While enabled, spec_draft attaches a pair of HIP events to
  * every contraction launch (they receive that kernel's begin / end time on the
  * caller's stream); nothing else changes.
- *   kernel: 0 = rows<=16 streaming kernel, 1..3 = dense kernel with 32/64/96-row state blocks,
+ *   kernel: 0 = rows<=16 streaming kernel (head_skinny_kernel),
+ *           1, 2 = narrow dense kernel head_gemm_kernel<MI,1,8> with MI = 2, 4 (32- / 64-row state blocks),
  *           4 = whole draft in one launch (rows / weight_rows summed over its contractions),
- *           5 = dense kernel with 160-row state blocks
+ *           1000 + 100 * MB + 2 * KT + VT = wide dense kernel head_gemm32_kernel<MB,2,KT,VT>
+ *           (32 * MB-row state blocks, per-lane top-k lists of KT entries, VT = 1 with short tiles)
  *   rows, weight_rows, k: the contraction is [rows, k] x [weight_rows, k]^T
  *                  (weight_rows counts head and fused next-projection rows together)
  *   ms: elapsed time between the two events */

@@ -449,7 +449,7 @@ static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, c
   *nparts = job.nparts;
   if (stage >= 0 && !out_head && (int64_t)R * job.nparts > m->part_rows_parts)
     return fail(SPEC_ESHAPE, "internal: partial workspace too small (%d rows x %d parts)", R, job.nparts);
-  const int slot = prof_slot(m, pl.mi == 2 ? 1 : (pl.mi == 4 ? 2 : (pl.mi == 6 ? 3 : 5)), R, job.n_head + job.n_proj, K);
+  const int slot = prof_slot(m, pl.ni == 1 ? (pl.mi == 2 ? 1 : 2) : 1000 + 50 * pl.mi + 2 * pl.kcap + (pl.ts != 16 ? 1 : 0), R, job.n_head + job.n_proj, K);
   HIP_TRY(launch_head_gemm(job, pl, st, EV0(slot), EV1(slot)));
   return SPEC_OK;
 }
