@@ -47,10 +47,10 @@ constexpr int NSET = PD + 1;
 constexpr int GD = 4;
 static_assert(GD <= NSET, "a state register set is reused NSET slabs later");
 
-#ifndef SPEC_TALL_COST
-#define SPEC_TALL_COST 1.35
-#endif
-constexpr double kTallSlabCost = SPEC_TALL_COST;
+// Cost of one tile with 128- / 160-row state blocks relative to one with 96-row blocks
+// (measured at the 7B shape: 54, 65 and 76 us per tile of a range).
+constexpr double kMidSlabCost = 1.2;
+constexpr double kTallSlabCost = 1.4;
 
 // Workgroup tiles of the two weight matrices for tiles of ts 16-row weight tiles.
 static int plan_tiles(int n_rows, int ts) { return ((n_rows + 15) / 16 + ts - 1) / ts; }
@@ -117,15 +117,20 @@ GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
     pl.mi = 6;
     fill_plan(pl, R, n_head, n_proj, n_cu);
     if (pl.kcap <= 4) {
-      // 96- or 160-row state blocks: the longest range decides the launch, a K slab of the
-      // taller block costs ~1.35x the shorter one's (more matrix work per byte from L2)
-      GemmPlan tall = pl;
-      tall.mi = 10;
-      fill_plan(tall, R, n_head, n_proj, n_cu);
+      // 96-, 128- or 160-row state blocks: the longest range decides the launch; a tile of a
+      // taller block costs more (measured per K slab, relative to the 96-row block), but less
+      // than its share of rows (more matrix work per byte from L2)
       const int total = (n_head + 255) / 256 + (n_proj + 255) / 256;
-      const double c96 = 1.0 * ((total + pl.n_ranges - 1) / pl.n_ranges);
-      const double c160 = kTallSlabCost * ((total + tall.n_ranges - 1) / tall.n_ranges);
-      if (c160 < c96) pl = tall;
+      double best = 1.0 * ((total + pl.n_ranges - 1) / pl.n_ranges);
+      const int cand_mi[2] = {8, 10};
+      const double cand_cost[2] = {kMidSlabCost, kTallSlabCost};
+      for (int c = 0; c < 2; ++c) {
+        GemmPlan alt = pl;
+        alt.mi = cand_mi[c];
+        fill_plan(alt, R, n_head, n_proj, n_cu);
+        const double cost = cand_cost[c] * ((total + alt.n_ranges - 1) / alt.n_ranges);
+        if (cost < best) { best = cost; pl = alt; }
+      }
     }
     shrink_tile(pl, R, n_head, n_proj, n_cu);
     return pl;
@@ -911,6 +916,8 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
     case 6 * 100 + 4 * 10 + 8:
       return vt ? launch_gemm32_t<3, 2, 8, true>(a, st, ev_start, ev_stop)
                 : launch_gemm32_t<3, 2, 8, false>(a, st, ev_start, ev_stop);
+    case 8 * 100 + 4 * 10 + 2: return vt ? hipErrorInvalidValue : launch_gemm32_t<4, 2, 2, false>(a, st, ev_start, ev_stop);
+    case 8 * 100 + 4 * 10 + 4: return vt ? hipErrorInvalidValue : launch_gemm32_t<4, 2, 4, false>(a, st, ev_start, ev_stop);
     case 10 * 100 + 4 * 10 + 2: return vt ? hipErrorInvalidValue : launch_gemm32_t<5, 2, 2, false>(a, st, ev_start, ev_stop);
     case 10 * 100 + 4 * 10 + 4: return vt ? hipErrorInvalidValue : launch_gemm32_t<5, 2, 4, false>(a, st, ev_start, ev_stop);
     default: return hipErrorInvalidValue;

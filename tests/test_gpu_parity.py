@@ -69,6 +69,9 @@ SMALL_BF16 = [
     # 5 K slabs = one steady group + tail, ragged vocabulary and rows; per-lane lists of 2 and of 4
     ("bf16_b31_tall_k2", 128, 320, 16500, 3, (5, 3, 2), 6, 31),   # 31, 155, 465
     ("bf16_b31_tall_k3", 128, 320, 16500, 3, (5, 3, 3), 6, 31),
+    # 128-row state blocks (310 rows against 80 tiles: one tile per range with three blocks, two with four)
+    ("bf16_b31_mid_k2", 128, 320, 20300, 3, (5, 2, 2), 6, 31),    # 31, 155, 310
+    ("bf16_b31_mid_k3", 128, 320, 20300, 3, (5, 2, 3), 6, 31),
     # the limits of the boundary: 4096 leaves with top-k 8 everywhere (rows 1, 8, 64, 512), eight stages,
     # a vocabulary smaller than one 16-row tile
     ("bf16_max_leaves", 64, 64, 300, 4, (8, 8, 8, 8), 64, 1),
