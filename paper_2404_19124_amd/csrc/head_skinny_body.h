@@ -55,7 +55,15 @@ __device__ __forceinline__ void skinny_prefetch(const HeadJob& p, int wg, int G,
   }
 }
 
-template <int NS, int DEPTH, bool EXACT>
+// AGENT: the results are read by other workgroups of the SAME launch (the fused draft) and
+// are stored at agent scope (written through); a stand-alone launch stores plainly.
+template <bool AGENT, typename T>
+__device__ __forceinline__ void skinny_put(T* p, T v) {
+  if (AGENT) store_agent(p, v);
+  else *p = v;
+}
+
+template <int NS, int DEPTH, bool EXACT, bool AGENT>
 __device__ __forceinline__ void skinny_run(const HeadJob& p, int wg, int G, u32x4 (&a)[DEPTH][NS],
                                            unsigned char* smem) {
   const int kt = p.kt, R = p.R;
@@ -160,7 +168,7 @@ __device__ __forceinline__ void skinny_run(const HeadJob& p, int wg, int G, u32x
               }
             } else {
               const int d2 = (tile - p.vt_head) * 16 + vi;
-              if (d2 < p.n_proj) store_agent(&p.out_proj[(int64_t)en * p.ld_proj + d2], sum);
+              if (d2 < p.n_proj) skinny_put<AGENT>(&p.out_proj[(int64_t)en * p.ld_proj + d2], sum);
             }
           }
         }
@@ -202,8 +210,8 @@ __device__ __forceinline__ void skinny_run(const HeadJob& p, int wg, int G, u32x
     s = row16_sum((m > SPEC_NEG_INF) ? s * __expf(m - mx) : 0.f);
     const int64_t slot = (int64_t)row * p.nparts + wg;
     if (row < R && src == 0) {
-      store_agent(&p.part.m[slot], mx);
-      store_agent(&p.part.s[slot], s);
+      skinny_put<AGENT>(&p.part.m[slot], mx);
+      skinny_put<AGENT>(&p.part.s[slot], s);
     }
 #pragma unroll
     for (int j = 0; j < kMaxTopK; ++j) {
@@ -218,8 +226,8 @@ __device__ __forceinline__ void skinny_run(const HeadJob& p, int wg, int G, u32x
           hi[kMaxTopK - 1] = kIdxNone;
         }
         if (row < R && src == j) {
-          store_agent(&p.part.val[slot * p.k_top + j], bv);
-          store_agent(&p.part.idx[slot * p.k_top + j], bi);
+          skinny_put<AGENT>(&p.part.val[slot * p.k_top + j], bv);
+          skinny_put<AGENT>(&p.part.idx[slot * p.k_top + j], bi);
         }
       }
     }

@@ -147,7 +147,7 @@ __device__ __attribute__((noinline)) int fused_head_phase(int idx_v, unsigned ta
   if (idx > 0) {
     if (!grid_barrier(J->barrier, target, J->timeout_ticks, reinterpret_cast<int*>(smem))) return 0;
   }
-  skinny_run<NS, DEPTH, true>(p, wg, G, a, smem + kFusedDescBytes);
+  skinny_run<NS, DEPTH, true, true>(p, wg, G, a, smem + kFusedDescBytes);
   return 1;
 }
 
@@ -158,7 +158,7 @@ __device__ __attribute__((noinline)) void fused_stage_phase(int i_v, unsigned ld
   const StageJob& sj = fused_job(job_v)->stage[i];
   const int G = gridDim.x;
   for (int r = blockIdx.x; r < sj.R; r += G)
-    stage_row<true, 1, kSkinnyWaves * 64>(sj, r, reinterpret_cast<float*>(smem + kFusedDescBytes));
+    stage_row<true, 1, kSkinnyWaves * 64, true>(sj, r, reinterpret_cast<float*>(smem + kFusedDescBytes));
 }
 
 __device__ __attribute__((noinline)) void fused_tree_phase(unsigned lds_v, unsigned job_v) {

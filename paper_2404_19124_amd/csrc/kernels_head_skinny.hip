@@ -39,7 +39,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void head_skinny_kernel(HeadJob 
   // already in flight while the states load
   u32x4 a[DEPTH][NS];
   skinny_prefetch<NS, DEPTH, EXACT>(p, blockIdx.x, gridDim.x, a);
-  skinny_run<NS, DEPTH, EXACT>(p, blockIdx.x, gridDim.x, a, smem);
+  skinny_run<NS, DEPTH, EXACT, false>(p, blockIdx.x, gridDim.x, a, smem);
 }
 
 template <int NS, int DEPTH, bool EXACT>

@@ -13,7 +13,10 @@ namespace specdraft {
 // a separate launch on the latency-critical batch-1 chain).
 // NCH = 8-element chunks per thread held in registers (D <= NCH * NT * 8).
 // `lds`: (NT / 256) * 32 + 32 words of scratch.  Contains workgroup barriers.
-template <bool BF16, int NCH, int NT>
+// AGENT: results are handed to other workgroups of the SAME launch (the fused draft): stored
+// at agent scope, i.e. written through, in 8-byte pieces.  A stand-alone launch stores whole
+// 16-byte slots and lets the L2 gather the eight rows that share a 128-byte line.
+template <bool BF16, int NCH, int NT, bool AGENT>
 __device__ __forceinline__ void stage_row(const StageJob& j, int r, float* lds) {
   float* scratch = lds;                 // NT / 64 <= 16 words
   const int tid = opaque_tid(), lane = tid & 63;
@@ -62,10 +65,18 @@ __device__ __forceinline__ void stage_row(const StageJob& j, int r, float* lds) 
 #pragma unroll
       for (int q = 0; q < kMaxTopK; ++q)
         if (lane == q && q < j.k_prev) {
-          store_agent(&j.prev_tok[(int64_t)parent * j.k_prev + q], ix[q]);
-          store_agent(&j.prev_logp[(int64_t)parent * j.k_prev + q], v[q] - lse);
+          if (AGENT) {
+            store_agent(&j.prev_tok[(int64_t)parent * j.k_prev + q], ix[q]);
+            store_agent(&j.prev_logp[(int64_t)parent * j.k_prev + q], v[q] - lse);
+          } else {
+            j.prev_tok[(int64_t)parent * j.k_prev + q] = ix[q];
+            j.prev_logp[(int64_t)parent * j.k_prev + q] = v[q] - lse;
+          }
         }
-      if (lane == 0) store_agent(&j.prev_lse[parent], lse);
+      if (lane == 0) {
+        if (AGENT) store_agent(&j.prev_lse[parent], lse);
+        else j.prev_lse[parent] = lse;
+      }
     }
   }
   tok = min(max(tok, 0), j.V - 1);  // a wild token from the caller must not leave the table
@@ -133,9 +144,13 @@ __device__ __forceinline__ void stage_row(const StageJob& j, int r, float* lds) 
         o.w = f32_to_bf16_bits(s[6]) | (f32_to_bf16_bits(s[7]) << 16);
         // tiled layout: row tile r/16, column fragment c/4, lane slot (c%4)*16 + r%16
         const int64_t slot = ((int64_t)(r >> 4) * (D / 32) + (c >> 2)) * 64 + ((c & 3) << 4) + (r & 15);
-        uint64_t* so = reinterpret_cast<uint64_t*>(j.state_out) + 2 * slot;
-        store_agent(so, (uint64_t)o.x | ((uint64_t)o.y << 32));
-        store_agent(so + 1, (uint64_t)o.z | ((uint64_t)o.w << 32));
+        if (AGENT) {
+          uint64_t* so = reinterpret_cast<uint64_t*>(j.state_out) + 2 * slot;
+          store_agent(so, (uint64_t)o.x | ((uint64_t)o.y << 32));
+          store_agent(so + 1, (uint64_t)o.z | ((uint64_t)o.w << 32));
+        } else {
+          reinterpret_cast<uint4*>(j.state_out)[slot] = o;
+        }
         if (j.state_dbg) reinterpret_cast<uint4*>(j.state_dbg)[((int64_t)r * D) / 8 + c] = o;
       } else {
         float* so = static_cast<float*>(j.state_out) + (int64_t)r * D + c * 8;
