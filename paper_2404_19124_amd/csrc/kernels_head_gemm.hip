@@ -92,6 +92,7 @@ static void shrink_tile(GemmPlan& pl, int R, int n_head, int n_proj, int n_cu) {
 GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
   GemmPlan pl;
   pl.ts = 4;
+  pl.ksplit = 1;
   if (R <= 32) { pl.mi = 2; pl.ni = 1; pl.kcap = 8; }
   // 33..64 rows against a long weight matrix (at least one 256-row tile per two CUs): the
   // wide kernel re-reads the states a quarter as often per weight byte as the narrow one
@@ -136,6 +137,15 @@ GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
     return pl;
   }
   fill_plan(pl, R, n_head, n_proj, n_cu);
+  // A projection alone is a short weight matrix: a few dozen workgroups, each with a long
+  // serial K loop and only its own prefetch depth in flight.  Splitting K over more
+  // workgroups multiplies the bytes in flight; the consumer adds the partial sums.
+  if (n_head == 0) {
+    const int cus = n_cu > 0 ? n_cu : 256;
+    while (pl.ksplit < kMaxKSplit && pl.m_tiles * pl.n_ranges * pl.ksplit * 2 <= 2 * cus &&
+           kt / KS / (pl.ksplit * 2) >= 8)
+      pl.ksplit *= 2;
+  }
   return pl;
 }
 
@@ -152,6 +162,8 @@ struct GemmArgs {
   int R, mt_total;
   int m_tiles, n_ranges, chunk;  // chunk = workgroups per XCD
   int ts;                        // 16-row weight tiles per workgroup tile (wide kernel)
+  int ksplit;                    // narrow kernel, store epilogue: workgroups per tile along K
+  int64_t out_part_stride;       // floats between the K parts' outputs
   int k_top;
   Partials part;
   int nparts;
@@ -174,14 +186,17 @@ __global__ __launch_bounds__(256, (MI <= 4 ? 2 : 1)) void head_gemm_kernel(GemmA
   const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
   if (seq >= p.chunk) return;
   const int wg = xcd * p.chunk + seq;
-  if (wg >= p.m_tiles * p.n_ranges) return;
-  const int range = wg / p.m_tiles, mtile = wg - range * p.m_tiles;
+  if (wg >= p.m_tiles * p.n_ranges * p.ksplit) return;
+  // K split (store epilogue only): part kpart of a tile covers slabs [slab0, slab0 + nslab)
+  const int kpart = wg % p.ksplit, wg2 = wg / p.ksplit;
+  const int range = wg2 / p.m_tiles, mtile = wg2 - range * p.m_tiles;
   const int total_tiles = p.n_tiles[0] + p.n_tiles[1];
   const int t0 = (int)((int64_t)range * total_tiles / p.n_ranges);
   const int t1 = (int)((int64_t)(range + 1) * total_tiles / p.n_ranges);
 
   const int kt = p.kt;
-  const int nslab = kt / KS;
+  const int slab0 = (int)((int64_t)kpart * (kt / KS) / p.ksplit);
+  const int nslab = (int)((int64_t)(kpart + 1) * (kt / KS) / p.ksplit) - slab0;
   // staging sources of this thread (the same for every tile of the range)
   const u32x4* sptr[SPT];
 #pragma unroll
@@ -189,7 +204,7 @@ __global__ __launch_bounds__(256, (MI <= 4 ? 2 : 1)) void head_gemm_kernel(GemmA
     const int i = s * 256 + tid;
     const int mtl = i / (KS * 64), rem = i % (KS * 64);
     const int mt = min(mtile * MI + mtl, p.mt_total - 1);
-    sptr[s] = p.b + (int64_t)mt * kt * 64 + rem;
+    sptr[s] = p.b + (int64_t)mt * kt * 64 + (int64_t)slab0 * KS * 64 + rem;
   }
 
   // weight fragment pointers of this wave for a given tile of the list
@@ -201,7 +216,7 @@ __global__ __launch_bounds__(256, (MI <= 4 ? 2 : 1)) void head_gemm_kernel(GemmA
     for (int ni = 0; ni < NI; ++ni) {
       ntv[ni] = (ntile * 4 + wave) * NI + ni;
       const int ntc = min(ntv[ni], p.nt_total[mat] - 1);
-      wp[ni] = p.w[mat] + (int64_t)ntc * kt * 64 + lane;
+      wp[ni] = p.w[mat] + (int64_t)ntc * kt * 64 + (int64_t)slab0 * KS * 64 + lane;
     }
   };
 
@@ -330,7 +345,7 @@ __global__ __launch_bounds__(256, (MI <= 4 ? 2 : 1)) void head_gemm_kernel(GemmA
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni) {
           const int v0 = cur_nt[ni] * 16 + grp * 4;
-          float* o = p.out[cur_mat] + (int64_t)r * p.ldo[cur_mat] + v0;
+          float* o = p.out[cur_mat] + kpart * p.out_part_stride + (int64_t)r * p.ldo[cur_mat] + v0;
           if (v0 + 3 < n_valid && (p.ldo[cur_mat] & 3) == 0) {
             *reinterpret_cast<float4*>(o) = make_float4(acc[mi][ni][0], acc[mi][ni][1], acc[mi][ni][2], acc[mi][ni][3]);
           } else {
@@ -896,7 +911,14 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
   a.m_tiles = pl.m_tiles;
   a.n_ranges = pl.n_ranges;
   a.ts = pl.ts;
-  a.chunk = (pl.m_tiles * pl.n_ranges + 7) / 8;
+  a.ksplit = 1;
+  if (pl.ksplit > 1) {
+    // only a projection alone, on the narrow kernel, with room for the parts
+    if (pl.ni != 1 || job.vt_head > 0 || job.proj_part_stride <= 0 || (job.proj_part_stride & 3)) return hipErrorInvalidValue;
+    a.ksplit = pl.ksplit;
+    a.out_part_stride = job.proj_part_stride;
+  }
+  a.chunk = (pl.m_tiles * pl.n_ranges * pl.ksplit + 7) / 8;
   a.k_top = job.k_top;
   a.part = job.part;
   a.nparts = job.nparts;

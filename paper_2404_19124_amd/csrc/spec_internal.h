@@ -64,6 +64,9 @@ struct HeadJob {
   // projection epilogue: out_proj[r * ld_proj + d]
   float* out_proj;
   int64_t ld_proj;
+  // a projection launched alone may be split along K (GemmPlan::ksplit): part q holds the sum over
+  // its K range at out_proj + q * proj_part_stride, and the consumer adds the parts in order
+  int64_t proj_part_stride;
 };
 
 // Rows <= 16: one persistent workgroup per CU, K split over its 16 waves,
@@ -85,7 +88,9 @@ struct GemmPlan {
   int m_tiles;       // blocks of state rows
   int n_ranges;      // ranges of weight-row tiles
   int nparts;        // ranges that hold head tiles = parts per row
+  int ksplit;        // parts of K (> 1 only for a projection alone on the narrow kernel)
 };
+constexpr int kMaxKSplit = 4;
 GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu);
 hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& plan, hipStream_t st, hipEvent_t ev_start = nullptr,
                             hipEvent_t ev_stop = nullptr);
@@ -117,7 +122,9 @@ struct StageJob {
   float* prev_logp;        // same layout, out
   float* prev_lse;         // [R/k_prev] out
   const int32_t* last_tok; // stage 0: [R]
-  const float* pz;         // [R/k_prev][D] projected parent state
+  const float* pz;         // [R/k_prev][D] projected parent state ...
+  int pz_parts;            // ... as the sum of this many partial projections (0 or 1: a single one),
+  int64_t pz_part_stride;  // pz_part_stride floats apart
   const void* emb;         // [V][D]
   const float* gamma;
   const float* beta;

@@ -262,7 +262,9 @@ extern "C" spec_status_t spec_create(const spec_config_t* cfg, const spec_weight
   TRY_FREE(dev_alloc(m, &m->state_in, m->bf16 ? (size_t)batch16 * E * 2 : 16));
   HIP_TRY_FREE(hipMemsetAsync(m->states, 0, (size_t)rows16 * D * m->esz, stream));
   if (m->bf16) HIP_TRY_FREE(hipMemsetAsync(m->state_in, 0, (size_t)batch16 * E * 2, stream));
-  for (int q = 0; q < 2; ++q) TRY_FREE(dev_alloc(m, &m->pz[q], (size_t)max_parent * D * 4));
+  // (the first projection may come as kMaxKSplit partial sums of max_batch rows each)
+  const int64_t pz_rows = max_parent > (int64_t)kMaxKSplit * cfg->max_batch ? max_parent : (int64_t)kMaxKSplit * cfg->max_batch;
+  for (int q = 0; q < 2; ++q) TRY_FREE(dev_alloc(m, &m->pz[q], (size_t)pz_rows * D * 4));
   m->part_rows_parts = partial_capacity(max_rows, V, m->n_cu);
   TRY_FREE(dev_alloc(m, &m->part.m, (size_t)m->part_rows_parts * 4));
   TRY_FREE(dev_alloc(m, &m->part.s, (size_t)m->part_rows_parts * 4));
@@ -428,7 +430,8 @@ static HeadJob make_head_job(const spec_model* m, int stage, int proj_stage, con
 
 static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, const void* b_src, bool b_rowmajor,
                                      int b_ld, int R, int k_top, float* out_head, float* out_proj, int* nparts,
-                                     hipStream_t st) {
+                                     hipStream_t st, int* proj_parts = nullptr) {
+  if (proj_parts) *proj_parts = 1;
   HeadJob job = make_head_job(m, stage, proj_stage, b_src, b_rowmajor, b_ld, R, k_top, out_head, out_proj);
   const int K = b_ld;
   if (skinny_fits(R, job.kt)) {
@@ -445,6 +448,11 @@ static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, c
     job.b_rowmajor = 0;
   }
   GemmPlan pl = plan_gemm(R, k_top, job.n_head, job.n_proj, job.kt, m->n_cu);
+  if (pl.ksplit > 1) {
+    if (!proj_parts) pl.ksplit = 1;  // the caller reads out_proj as it is
+    else job.proj_part_stride = (int64_t)R * job.ld_proj;
+  }
+  if (proj_parts) *proj_parts = pl.ksplit;
   job.nparts = pl.nparts > 0 ? pl.nparts : 1;
   *nparts = job.nparts;
   if (stage >= 0 && !out_head && (int64_t)R * job.nparts > m->part_rows_parts)
@@ -589,10 +597,10 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
     m->barrier_value += (unsigned)kFusedBarriers(n);
     m->clocks_n = 2 * n + 4;
   } else {
-    int nparts = 1;
+    int nparts = 1, pz0_parts = 1;
     // projection of the base model's state for stage 1
     if (m->bf16) {
-      spec_status_t s = run_contraction(m, -1, 0, state, true, E, batch, 0, nullptr, m->pz[0], &nparts, st);
+      spec_status_t s = run_contraction(m, -1, 0, state, true, E, batch, 0, nullptr, m->pz[0], &nparts, st, &pz0_parts);
       if (s != SPEC_OK) return s;
     } else {
       HIP_TRY(launch_gemm_f32(static_cast<const float*>(state), E, static_cast<const float*>(m->proj[0]), E, m->pz[0],
@@ -600,7 +608,12 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
     }
 
     for (int i = 0; i < n; ++i) {
-      HIP_TRY(launch_stage(stage_job(i, nparts), st));
+      StageJob sj = stage_job(i, nparts);
+      if (i == 0) {
+        sj.pz_parts = pz0_parts;
+        sj.pz_part_stride = (int64_t)batch * D;
+      }
+      HIP_TRY(launch_stage(sj, st));
       const int proj_next = i + 1 < n ? i + 1 : -1;
       if (m->bf16) {
         spec_status_t s = run_contraction(m, i, proj_next, m->states, false, D, (int)R[i], top_k[i], nullptr,

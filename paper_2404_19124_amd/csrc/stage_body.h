@@ -32,8 +32,15 @@ __device__ __forceinline__ void stage_row(const StageJob& j, int r, float* lds) 
   for (int ci = 0; ci < NCH; ++ci) {
     const int c = tid + ci * NT;
     if (c < nchunk) {
-      const float4 p0 = *reinterpret_cast<const float4*>(pz + c * 8);
-      const float4 p1 = *reinterpret_cast<const float4*>(pz + c * 8 + 4);
+      float4 p0 = *reinterpret_cast<const float4*>(pz + c * 8);
+      float4 p1 = *reinterpret_cast<const float4*>(pz + c * 8 + 4);
+      for (int q = 1; q < j.pz_parts; ++q) {  // a projection split along K: add the parts in order
+        const float* pq = pz + q * j.pz_part_stride + c * 8;
+        const float4 q0 = *reinterpret_cast<const float4*>(pq);
+        const float4 q1 = *reinterpret_cast<const float4*>(pq + 4);
+        p0.x += q0.x; p0.y += q0.y; p0.z += q0.z; p0.w += q0.w;
+        p1.x += q1.x; p1.y += q1.y; p1.z += q1.z; p1.w += q1.w;
+      }
       const float4 g0 = *reinterpret_cast<const float4*>(j.gamma + c * 8);
       const float4 g1 = *reinterpret_cast<const float4*>(j.gamma + c * 8 + 4);
       const float4 b0 = *reinterpret_cast<const float4*>(j.beta + c * 8);

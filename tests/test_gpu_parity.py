@@ -72,6 +72,9 @@ SMALL_BF16 = [
     # 128-row state blocks (310 rows against 80 tiles: one tile per range with three blocks, two with four)
     ("bf16_b31_mid_k2", 128, 320, 20300, 3, (5, 2, 2), 6, 31),    # 31, 155, 310
     ("bf16_b31_mid_k3", 128, 320, 20300, 3, (5, 2, 3), 6, 31),
+    # first projection split along K (long E, more than 16 rows): four parts, and two parts with two row blocks
+    ("bf16_b20_long_e", 2048, 64, 300, 2, (2, 2), 4, 20),
+    ("bf16_b40_long_e", 1024, 128, 300, 2, (3, 2), 6, 40),
     # the limits of the boundary: 4096 leaves with top-k 8 everywhere (rows 1, 8, 64, 512), eight stages,
     # a vocabulary smaller than one 16-row tile
     ("bf16_max_leaves", 64, 64, 300, 4, (8, 8, 8, 8), 64, 1),
