@@ -242,6 +242,30 @@ spec_status_t spec_fused_phase_us(spec_model_t* m, float* us, int32_t cap, int32
  * SPEC_EINVAL on bad arguments (nothing is launched). */
 spec_status_t spec_copy_probe(const void* src, void* dst, int64_t bytes, void* hip_stream);
 
+/* Host-only query (no device, no model, no HIP call): the launch plan the library uses for ONE
+ * contraction of the draft (Sec. 3.1: a stage's vocabulary head, with the next stage's state
+ * projection riding in the same launch) in the bf16 configuration:
+ *   rows    state rows (>= 1);  k  their width (multiple of 64)
+ *   n_head  head rows (vocabulary), 0 = no head;  k_top  entries kept per row (1..8; ignored without a head)
+ *   n_proj  projection rows, 0 = none (n_head + n_proj >= 1)
+ *   n_cu    compute units of the device (256 on MI355X)
+ * For checking the planning logic without a GPU and for reading profiles. */
+typedef struct {
+  int32_t kernel;       /* as spec_launch_record_t.kernel */
+  int32_t block_rows;   /* state rows per workgroup */
+  int32_t tile_rows;    /* weight rows per workgroup tile */
+  int32_t row_blocks;   /* blocks of state rows: row_blocks * block_rows >= rows */
+  int32_t ranges;       /* workgroups per row block; each owns a contiguous range of the tiles */
+  int32_t tiles;        /* tiles of both weight matrices together */
+  int32_t parts;        /* partial (log-sum-exp, top-k) results per row handed to the merge */
+  int32_t k_split;      /* workgroups per tile along k (projection alone), 1 otherwise */
+  int32_t workgroups;   /* row_blocks * ranges * k_split */
+  int32_t lds_bytes;    /* dynamic LDS per workgroup */
+} spec_plan_t;
+/* SPEC_EINVAL: arguments out of range; SPEC_ESHAPE: no kernel instance serves the plan (a library bug). */
+spec_status_t spec_plan_contraction(int32_t rows, int32_t k, int32_t n_head, int32_t k_top, int32_t n_proj,
+                                    int32_t n_cu, spec_plan_t* out);
+
 /* Reads back the mix weights and epsilon the model uses (after defaults were applied). */
 spec_status_t spec_model_scalars(const spec_model_t* m, float* state_weight, float* emb_weight,
                                  float* ln_eps);

@@ -22,7 +22,7 @@ SPEC_OK, SPEC_EINVAL, SPEC_ESHAPE, SPEC_EDTYPE, SPEC_ENOMEM, SPEC_EHIP = 0, -1, 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecdraft.so")
 
 EXPORTS = ["spec_create", "spec_destroy", "spec_draft", "spec_verify", "spec_head_logp", "spec_model_scalars",
-           "spec_profile_enable", "spec_profile_read", "spec_copy_probe", "spec_set_fused", "spec_fused_timeout", "spec_fused_phase_us", "spec_tree_metadata", "spec_advance", "spec_last_error", "spec_version"]
+           "spec_profile_enable", "spec_profile_read", "spec_copy_probe", "spec_set_fused", "spec_fused_timeout", "spec_fused_phase_us", "spec_tree_metadata", "spec_advance", "spec_plan_contraction", "spec_last_error", "spec_version"]
 
 
 class SpecError(RuntimeError):
@@ -40,6 +40,11 @@ class spec_config_t(C.Structure):
 class spec_weights_t(C.Structure):
     _fields_ = [("proj", C.POINTER(C.c_void_p)), ("emb", C.POINTER(C.c_void_p)), ("head", C.POINTER(C.c_void_p)),
                 ("ln_gamma", C.POINTER(C.c_void_p)), ("ln_beta", C.POINTER(C.c_void_p))]
+
+
+class spec_plan_t(C.Structure):
+    _fields_ = [(name, C.c_int32) for name in ("kernel", "block_rows", "tile_rows", "row_blocks", "ranges", "tiles",
+                                               "parts", "k_split", "workgroups", "lds_bytes")]
 
 
 class spec_debug_t(C.Structure):
@@ -82,6 +87,8 @@ def lib() -> C.CDLL:
         l.spec_profile_enable.argtypes = [C.c_void_p, C.c_int32]
         l.spec_profile_read.restype = C.c_int
         l.spec_profile_read.argtypes = [C.c_void_p, C.POINTER(spec_launch_record_t), C.c_int32, C.POINTER(C.c_int32)]
+        l.spec_plan_contraction.restype = C.c_int
+        l.spec_plan_contraction.argtypes = [C.c_int32] * 6 + [C.POINTER(spec_plan_t)]
         l.spec_set_fused.restype = C.c_int
         l.spec_set_fused.argtypes = [C.c_void_p, C.c_int32]
         l.spec_fused_timeout.restype = C.c_int
@@ -251,6 +258,13 @@ def spec_advance(hidden: torch.Tensor, best_cand: torch.Tensor, accept_len: torc
     dtype = {torch.float32: SPEC_F32, torch.bfloat16: SPEC_BF16}[hidden.dtype]
     _check(lib().spec_advance(_ptr(hidden), dtype, b, Bc, n1 - 1, E, _ptr(best_cand), _ptr(accept_len),
                               _ptr(out_tokens), _ptr(next_state), _ptr(next_tok), _stream_ptr(stream)))
+
+
+def spec_plan_contraction(rows: int, k: int, n_head: int, k_top: int, n_proj: int, n_cu: int = 256) -> dict:
+    """The launch plan of one contraction (host-only: needs no GPU)."""
+    out = spec_plan_t()
+    _check(lib().spec_plan_contraction(int(rows), int(k), int(n_head), int(k_top), int(n_proj), int(n_cu), C.byref(out)))
+    return {name: int(getattr(out, name)) for name, _ in spec_plan_t._fields_}
 
 
 def spec_copy_probe(src: torch.Tensor, dst: torch.Tensor, stream=None) -> int:

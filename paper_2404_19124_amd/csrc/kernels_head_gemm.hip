@@ -849,9 +849,12 @@ static size_t gemm_smem(int mi, int kcap) {
   return slabs > merge ? slabs : merge;
 }
 
+// dry: only answer whether this instance exists and how much LDS it takes (no HIP call)
 template <int MI, int NI, int KT>
-static hipError_t launch_gemm_t(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
+static hipError_t launch_gemm_t(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop,
+                                size_t* dry) {
   const size_t smem = gemm_smem(MI, KT);
+  if (dry) { *dry = smem; return hipSuccess; }
   static bool attr_set = false;  // per instantiation
   if (!attr_set && smem > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_gemm_kernel<MI, NI, KT>),
@@ -864,8 +867,10 @@ static hipError_t launch_gemm_t(const GemmArgs& a, hipStream_t st, hipEvent_t ev
 }
 
 template <int MB, int NB, int KT, bool VT>
-static hipError_t launch_gemm32_t(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
+static hipError_t launch_gemm32_t(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop,
+                                  size_t* dry) {
   const size_t smem = gemm_smem(2 * MB, KT);
+  if (dry) { *dry = smem; return hipSuccess; }
   static bool attr_set = false;  // per instantiation
   if (!attr_set && smem > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_gemm32_kernel<MB, NB, KT, VT>),
@@ -879,7 +884,7 @@ static hipError_t launch_gemm32_t(const GemmArgs& a, hipStream_t st, hipEvent_t 
 }
 
 hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t st, hipEvent_t ev_start,
-                            hipEvent_t ev_stop) {
+                            hipEvent_t ev_stop, size_t* dry) {
   GemmArgs a;
   memset(&a, 0, sizeof(a));
   int nm = 0;
@@ -926,22 +931,22 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
   const int key = pl.mi * 100 + pl.ni * 10 + pl.kcap;
   const bool vt = pl.ni == 4 && pl.ts != 16;  // wide kernel with short tiles
   switch (key) {
-    case 2 * 100 + 1 * 10 + 8: return launch_gemm_t<2, 1, 8>(a, st, ev_start, ev_stop);
-    case 4 * 100 + 1 * 10 + 8: return launch_gemm_t<4, 1, 8>(a, st, ev_start, ev_stop);
-    case 4 * 100 + 4 * 10 + 8: return launch_gemm32_t<2, 2, 8, true>(a, st, ev_start, ev_stop);
+    case 2 * 100 + 1 * 10 + 8: return launch_gemm_t<2, 1, 8>(a, st, ev_start, ev_stop, dry);
+    case 4 * 100 + 1 * 10 + 8: return launch_gemm_t<4, 1, 8>(a, st, ev_start, ev_stop, dry);
+    case 4 * 100 + 4 * 10 + 8: return launch_gemm32_t<2, 2, 8, true>(a, st, ev_start, ev_stop, dry);
     case 6 * 100 + 4 * 10 + 2:
-      return vt ? launch_gemm32_t<3, 2, 2, true>(a, st, ev_start, ev_stop)
-                : launch_gemm32_t<3, 2, 2, false>(a, st, ev_start, ev_stop);
+      return vt ? launch_gemm32_t<3, 2, 2, true>(a, st, ev_start, ev_stop, dry)
+                : launch_gemm32_t<3, 2, 2, false>(a, st, ev_start, ev_stop, dry);
     case 6 * 100 + 4 * 10 + 4:
-      return vt ? launch_gemm32_t<3, 2, 4, true>(a, st, ev_start, ev_stop)
-                : launch_gemm32_t<3, 2, 4, false>(a, st, ev_start, ev_stop);
+      return vt ? launch_gemm32_t<3, 2, 4, true>(a, st, ev_start, ev_stop, dry)
+                : launch_gemm32_t<3, 2, 4, false>(a, st, ev_start, ev_stop, dry);
     case 6 * 100 + 4 * 10 + 8:
-      return vt ? launch_gemm32_t<3, 2, 8, true>(a, st, ev_start, ev_stop)
-                : launch_gemm32_t<3, 2, 8, false>(a, st, ev_start, ev_stop);
-    case 8 * 100 + 4 * 10 + 2: return vt ? hipErrorInvalidValue : launch_gemm32_t<4, 2, 2, false>(a, st, ev_start, ev_stop);
-    case 8 * 100 + 4 * 10 + 4: return vt ? hipErrorInvalidValue : launch_gemm32_t<4, 2, 4, false>(a, st, ev_start, ev_stop);
-    case 10 * 100 + 4 * 10 + 2: return vt ? hipErrorInvalidValue : launch_gemm32_t<5, 2, 2, false>(a, st, ev_start, ev_stop);
-    case 10 * 100 + 4 * 10 + 4: return vt ? hipErrorInvalidValue : launch_gemm32_t<5, 2, 4, false>(a, st, ev_start, ev_stop);
+      return vt ? launch_gemm32_t<3, 2, 8, true>(a, st, ev_start, ev_stop, dry)
+                : launch_gemm32_t<3, 2, 8, false>(a, st, ev_start, ev_stop, dry);
+    case 8 * 100 + 4 * 10 + 2: return vt ? hipErrorInvalidValue : launch_gemm32_t<4, 2, 2, false>(a, st, ev_start, ev_stop, dry);
+    case 8 * 100 + 4 * 10 + 4: return vt ? hipErrorInvalidValue : launch_gemm32_t<4, 2, 4, false>(a, st, ev_start, ev_stop, dry);
+    case 10 * 100 + 4 * 10 + 2: return vt ? hipErrorInvalidValue : launch_gemm32_t<5, 2, 2, false>(a, st, ev_start, ev_stop, dry);
+    case 10 * 100 + 4 * 10 + 4: return vt ? hipErrorInvalidValue : launch_gemm32_t<5, 2, 4, false>(a, st, ev_start, ev_stop, dry);
     default: return hipErrorInvalidValue;
   }
 }

@@ -57,8 +57,10 @@ static hipError_t launch_skinny_t(const HeadJob& job, int grid, size_t smem, hip
   return hipGetLastError();
 }
 
+size_t skinny_lds_bytes(int R, int kt) { return skinny_state_bytes(R, kt) + kSkinnyLdsP; }
+
 hipError_t launch_head_skinny(const HeadJob& job, int n_cu, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
-  const size_t smem = skinny_state_bytes(job.R, job.kt) + kSkinnyLdsP;
+  const size_t smem = skinny_lds_bytes(job.R, job.kt);
   const int grid = skinny_grid(n_cu);
   // K = 512 * NS gets an exact instantiation with as many tiles in flight as 16 fragments allow
   switch (job.kt % kSkinnyWaves == 0 ? job.kt / kSkinnyWaves : 0) {

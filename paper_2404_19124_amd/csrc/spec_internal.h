@@ -73,6 +73,7 @@ struct HeadJob {
 // weights streamed tile by tile straight into registers.  nparts = grid size.
 bool skinny_fits(int R, int kt);
 int skinny_grid(int n_cu);
+size_t skinny_lds_bytes(int R, int kt);   // dynamic LDS of one workgroup
 // ev_start / ev_stop (may be null) receive the kernel's own begin / end timestamps.
 hipError_t launch_head_skinny(const HeadJob& job, int n_cu, hipStream_t st, hipEvent_t ev_start = nullptr,
                               hipEvent_t ev_stop = nullptr);
@@ -92,8 +93,10 @@ struct GemmPlan {
 };
 constexpr int kMaxKSplit = 4;
 GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu);
+// dry != nullptr: nothing is launched (no HIP call at all); the result says whether a kernel
+// instance exists for the plan, and *dry receives its LDS bytes.
 hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& plan, hipStream_t st, hipEvent_t ev_start = nullptr,
-                            hipEvent_t ev_stop = nullptr);
+                            hipEvent_t ev_stop = nullptr, size_t* dry = nullptr);
 
 // ---- contraction, float32 (correctness configuration) ---------------------
 // out[r * ldo + v] = sum_k a[r * lda + k] * w[v * ldw + k]

@@ -361,6 +361,59 @@ extern "C" spec_status_t spec_profile_read(spec_model_t* m, spec_launch_record_t
   return SPEC_OK;
 }
 
+extern "C" spec_status_t spec_plan_contraction(int32_t rows, int32_t k, int32_t n_head, int32_t k_top, int32_t n_proj,
+                                               int32_t n_cu, spec_plan_t* out) {
+  if (!out) return fail(SPEC_EINVAL, "out is NULL");
+  if (rows < 1 || k < 64 || k % 64) return fail(SPEC_EINVAL, "rows = %d, k = %d: need rows >= 1, k a positive multiple of 64", rows, k);
+  if (n_head < 0 || n_proj < 0 || n_head + (int64_t)n_proj < 1)
+    return fail(SPEC_EINVAL, "n_head = %d, n_proj = %d: need at least one weight row", n_head, n_proj);
+  if (n_head > 0 && (k_top < 1 || k_top > kMaxTopK)) return fail(SPEC_EINVAL, "k_top = %d outside [1, %d]", k_top, kMaxTopK);
+  if (n_cu < 1) return fail(SPEC_EINVAL, "n_cu = %d must be >= 1", n_cu);
+  memset(out, 0, sizeof(*out));
+  const int kt = k / 32;
+  if (skinny_fits(rows, kt)) {
+    out->kernel = 0;
+    out->block_rows = 16;
+    out->tile_rows = 16;
+    out->row_blocks = 1;
+    out->ranges = skinny_grid(n_cu);
+    out->tiles = (n_head + 15) / 16 + (n_proj + 15) / 16;
+    out->parts = skinny_grid(n_cu);
+    out->k_split = 1;
+    out->workgroups = skinny_grid(n_cu);
+    out->lds_bytes = (int32_t)skinny_lds_bytes(rows, kt);
+    return SPEC_OK;
+  }
+  GemmPlan pl = plan_gemm(rows, n_head > 0 ? k_top : 0, n_head, n_proj, kt, n_cu);
+  HeadJob job;
+  memset(&job, 0, sizeof(job));
+  job.kt = kt;
+  job.R = rows;
+  job.k_top = n_head > 0 ? k_top : 0;
+  job.n_head = n_head;
+  job.vt_head = (n_head + 15) / 16;
+  job.n_proj = n_proj;
+  job.vt_proj = (n_proj + 15) / 16;
+  job.ld_head = n_head;
+  job.ld_proj = n_proj;
+  job.proj_part_stride = (int64_t)rows * n_proj;
+  size_t lds = 0;
+  if (launch_head_gemm(job, pl, nullptr, nullptr, nullptr, &lds) != hipSuccess)
+    return fail(SPEC_ESHAPE, "no kernel instance for %d-row blocks, %d weight rows per wave, top-k lists of %d, tiles of %d",
+                16 * pl.mi, 16 * pl.ni, pl.kcap, 16 * pl.ts);
+  out->kernel = pl.ni == 1 ? (pl.mi == 2 ? 1 : 2) : 1000 + 50 * pl.mi + 2 * pl.kcap + (pl.ts != 16 ? 1 : 0);
+  out->block_rows = 16 * pl.mi;
+  out->tile_rows = 16 * pl.ts;
+  out->row_blocks = pl.m_tiles;
+  out->ranges = pl.n_ranges;
+  out->tiles = ((n_head + 15) / 16 + pl.ts - 1) / pl.ts + ((n_proj + 15) / 16 + pl.ts - 1) / pl.ts;
+  out->parts = pl.nparts;
+  out->k_split = pl.ksplit;
+  out->workgroups = pl.m_tiles * pl.n_ranges * pl.ksplit;
+  out->lds_bytes = (int32_t)lds;
+  return SPEC_OK;
+}
+
 extern "C" spec_status_t spec_copy_probe(const void* src, void* dst, int64_t bytes, void* hip_stream) {
   if (!src || !dst) return fail(SPEC_EINVAL, "a required pointer is NULL");
   if (bytes <= 0 || bytes % 16) return fail(SPEC_EINVAL, "bytes = %lld must be a positive multiple of 16", (long long)bytes);
