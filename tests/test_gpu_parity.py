@@ -268,6 +268,54 @@ def test_draft_is_deterministic_and_reusable():
     assert np.array_equal(step2.cand_leaf.cpu().numpy(), od.cand_leaf)
 
 
+@pytest.mark.parametrize("batch", [1, 24])
+def test_draft_and_verify_replay_from_a_hip_graph(batch):
+    """The step only enqueues kernels, so a caller may capture it in a HIP graph: every replay, with the
+    program's own eager work and synchronisations in between, reproduces the eager step (batch 1: the
+    streaming kernels; batch 24: the dense ones with the split first projection)."""
+    wl = W.Workload("graph", 1024, 128, 2049, 3, (4, 3, 2), 10, batch, "bf16", "f32", 0.6, seed=9, emb_std=0.3)
+    gen = W.make_generator(9)
+    w = {k: [t.cuda() for t in v] for k, v in W.make_speculator(wl, gen).items()}
+    step = Step(wl, w)
+    inputs = []
+    for _ in range(3):
+        state, last = W.make_draft_inputs(wl, gen)
+        logits = torch.randn((wl.batch, wl.B, wl.n_predict + 1, wl.vocab), generator=gen)
+        inputs.append((state.cuda(), last.cuda(), logits.cuda()))
+    outs = ("cand_tokens", "cand_scores", "cand_leaf", "greedy", "accept_len", "best_cand", "out_tokens", "n_out")
+    eager = []
+    for state, last, logits in inputs:
+        step.draft(state, last)
+        step.verify(logits)
+        torch.cuda.synchronize()
+        eager.append([getattr(step, name).clone() for name in outs])
+    s_state, s_last, s_logits = (t.clone() for t in inputs[0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):      # a warm-up on the capture stream, as torch asks for
+        step.draft(s_state, s_last)
+        step.verify(s_logits)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step.draft(s_state, s_last)
+        step.verify(s_logits)
+    for rep in range(2):
+        for (state, last, logits), want in zip(inputs, eager):
+            s_state.copy_(state)
+            s_last.copy_(last)
+            s_logits.copy_(logits)
+            graph.replay()
+            torch.cuda.synchronize()
+            for name, ref in zip(outs, want):
+                assert torch.equal(getattr(step, name), ref), (name, rep)
+            # eager work of the program between the replays
+            step.draft(inputs[rep][0], inputs[rep][1])
+            torch.cuda.synchronize()
+    step.close()
+
+
 def test_no_token_conditioning_mode_and_tied_weights():
     wl = W.Workload("medusa", 128, 128, 600, 3, (3, 3, 2), 18, 2, "bf16", "f32", 0.6, seed=4, emb_std=0.3)
     rep, step, od, ov = run_workload(wl, w_s=1.0, w_e=0.0, gen_device="cpu")
