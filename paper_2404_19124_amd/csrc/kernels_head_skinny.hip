@@ -57,6 +57,11 @@ static hipError_t launch_skinny_t(const HeadJob& job, int grid, size_t smem, hip
   return hipGetLastError();
 }
 
+int skinny_fold_rows(int D) {
+  constexpr int NT = kSkinnyWaves * 64;
+  return (D > 0 && D % 512 == 0 && D / 8 <= NT) ? NT / (D / 8) : 0;
+}
+
 size_t skinny_lds_bytes(int R, int kt) { return skinny_state_bytes(R, kt) + kSkinnyLdsP; }
 
 hipError_t launch_head_skinny(const HeadJob& job, int n_cu, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {

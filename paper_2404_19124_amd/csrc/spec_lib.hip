@@ -483,10 +483,12 @@ static HeadJob make_head_job(const spec_model* m, int stage, int proj_stage, con
 
 static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, const void* b_src, bool b_rowmajor,
                                      int b_ld, int R, int k_top, float* out_head, float* out_proj, int* nparts,
-                                     hipStream_t st, int* proj_parts = nullptr) {
+                                     hipStream_t st, int* proj_parts = nullptr, const FoldJob* fold = nullptr) {
   if (proj_parts) *proj_parts = 1;
   HeadJob job = make_head_job(m, stage, proj_stage, b_src, b_rowmajor, b_ld, R, k_top, out_head, out_proj);
   const int K = b_ld;
+  if (fold && !skinny_fits(R, job.kt)) return fail(SPEC_ESHAPE, "internal: folded stage on a contraction of %d rows", R);
+  if (fold) job.fold = *fold;
   if (skinny_fits(R, job.kt)) {
     job.nparts = skinny_grid(m->n_cu);
     *nparts = job.nparts;
@@ -666,11 +668,25 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
         sj.pz_parts = pz0_parts;
         sj.pz_part_stride = (int64_t)batch * D;
       }
-      HIP_TRY(launch_stage(sj, st));
+      // First stage of one or two sequences: its rows (token = the last sampled one, no merge) are
+      // computed inside the head's streaming kernel instead of by a launch of their own.
+      FoldJob fold;
+      memset(&fold, 0, sizeof(fold));
+      const bool folded = i == 0 && m->bf16 && !dbg && skinny_fits((int)R[0], D / 32) && (int)R[0] <= skinny_fold_rows(D);
+      if (folded) {
+        fold.enabled = 1;
+        fold.D = D; fold.V = V;
+        fold.pz = sj.pz; fold.pz_parts = sj.pz_parts > 0 ? sj.pz_parts : 1; fold.pz_part_stride = sj.pz_part_stride;
+        fold.tok = last_tok;
+        fold.emb = sj.emb; fold.gamma = sj.gamma; fold.beta = sj.beta;
+        fold.w_s = sj.w_s; fold.w_e = sj.w_e; fold.eps = sj.eps;
+      } else {
+        HIP_TRY(launch_stage(sj, st));
+      }
       const int proj_next = i + 1 < n ? i + 1 : -1;
       if (m->bf16) {
         spec_status_t s = run_contraction(m, i, proj_next, m->states, false, D, (int)R[i], top_k[i], nullptr,
-                                          m->pz[(i + 1) & 1], &nparts, st);
+                                          m->pz[(i + 1) & 1], &nparts, st, nullptr, folded ? &fold : nullptr);
         if (s != SPEC_OK) return s;
       } else {
         const float* sf = static_cast<const float*>(m->states);

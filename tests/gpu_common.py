@@ -81,6 +81,19 @@ def run_workload(wl: W.Workload, ln_affine: str = "identity", gen_device: str = 
     for note in rep.notes[:5]:
         log("    " + note)
 
+    # The debug outputs above are not free of side effects on the launch sequence (with them the first
+    # stage always gets a launch of its own): the configuration the benchmark times is the one WITHOUT
+    # them, and it must produce the same candidates (same tokens; scores up to the order of two block sums).
+    if fused is None and w_s < 0 and not tied:
+        plain = Step(wl, w_dev)
+        plain.draft(state_d, last_d)
+        torch.cuda.synchronize()
+        assert torch.equal(plain.cand_tokens, step.cand_tokens), "candidates differ between debug and plain run"
+        assert torch.equal(plain.cand_leaf, step.cand_leaf)
+        assert (plain.cand_scores - step.cand_scores).abs().max().item() < 2e-3
+        plain.close()
+        log("  plain (benchmark) configuration reproduces the candidates")
+
     ov = None
     if check_verify:
         # candidates fed to both verifies: the oracle's where it ran, seeded random tokens elsewhere
