@@ -377,6 +377,25 @@ def test_head_logp_entry_point_matches_oracle():
         assert np.allclose(np.exp(got).sum(-1), 1.0, atol=1e-4)
 
 
+@pytest.mark.parametrize("rows,V", [(48, 33000), (120, 33000), (300, 20300), (465, 16500)])
+def test_head_logp_through_the_wide_kernels_store_epilogue(rows, V):
+    """Full log-softmax rows through the wide dense kernel's store epilogue for the head matrix: 64-row
+    blocks with short tiles, 96-row blocks with short tiles, 128- and 160-row blocks."""
+    wl = W.Workload("logp_wide", 128, 320, V, 2, (3, 2), 6, 160, "bf16", "f32", 0.6, seed=12)
+    gen = W.make_generator(12)
+    w = W.make_speculator(wl, gen)
+    step = Step(wl, {k: [t.cuda() for t in v] for k, v in w.items()})
+    s = torch.randn(rows, wl.inner_dim, generator=gen).to(torch.bfloat16)
+    out = torch.empty((rows, wl.vocab), dtype=torch.float32, device="cuda")
+    B.spec_head_logp(step.model, 0, s.cuda(), out)
+    torch.cuda.synchronize()
+    want, _ = O.log_softmax(O.head_logits(s.float().numpy(), W.to_numpy_f32(w["head"][0])))
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.abs(got - want).max() < 2e-3
+    assert np.allclose(np.exp(got).sum(-1), 1.0, atol=1e-4)
+    step.close()
+
+
 def test_runtime_argument_errors():
     wl = W.Workload("err", 64, 64, 100, 2, (2, 2), 4, 2, "bf16", "f32", 0.5)
     gen = W.make_generator(0)
