@@ -79,7 +79,7 @@ static void fill_plan(GemmPlan& pl, int R, int n_head, int n_proj, int n_cu) {
 // the matrix cores or the L2, and more K loops only cost: measured.)
 static void shrink_tile(GemmPlan& pl, int R, int n_head, int n_proj, int n_cu) {
   const int per16 = (plan_tiles(n_head, 16) + plan_tiles(n_proj, 16) + pl.n_ranges - 1) / pl.n_ranges;
-  if (per16 > 1 || pl.mi > 6) return;
+  if (per16 > 1) return;
   for (int ts = 4; ts < 16; ++ts) {
     GemmPlan c = pl;
     c.ts = ts;
@@ -943,10 +943,18 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
     case 6 * 100 + 4 * 10 + 8:
       return vt ? launch_gemm32_t<3, 2, 8, true>(a, st, ev_start, ev_stop, dry)
                 : launch_gemm32_t<3, 2, 8, false>(a, st, ev_start, ev_stop, dry);
-    case 8 * 100 + 4 * 10 + 2: return vt ? hipErrorInvalidValue : launch_gemm32_t<4, 2, 2, false>(a, st, ev_start, ev_stop, dry);
-    case 8 * 100 + 4 * 10 + 4: return vt ? hipErrorInvalidValue : launch_gemm32_t<4, 2, 4, false>(a, st, ev_start, ev_stop, dry);
-    case 10 * 100 + 4 * 10 + 2: return vt ? hipErrorInvalidValue : launch_gemm32_t<5, 2, 2, false>(a, st, ev_start, ev_stop, dry);
-    case 10 * 100 + 4 * 10 + 4: return vt ? hipErrorInvalidValue : launch_gemm32_t<5, 2, 4, false>(a, st, ev_start, ev_stop, dry);
+    case 8 * 100 + 4 * 10 + 2:
+      return vt ? launch_gemm32_t<4, 2, 2, true>(a, st, ev_start, ev_stop, dry)
+                : launch_gemm32_t<4, 2, 2, false>(a, st, ev_start, ev_stop, dry);
+    case 8 * 100 + 4 * 10 + 4:
+      return vt ? launch_gemm32_t<4, 2, 4, true>(a, st, ev_start, ev_stop, dry)
+                : launch_gemm32_t<4, 2, 4, false>(a, st, ev_start, ev_stop, dry);
+    case 10 * 100 + 4 * 10 + 2:
+      return vt ? launch_gemm32_t<5, 2, 2, true>(a, st, ev_start, ev_stop, dry)
+                : launch_gemm32_t<5, 2, 2, false>(a, st, ev_start, ev_stop, dry);
+    case 10 * 100 + 4 * 10 + 4:
+      return vt ? launch_gemm32_t<5, 2, 4, true>(a, st, ev_start, ev_stop, dry)
+                : launch_gemm32_t<5, 2, 4, false>(a, st, ev_start, ev_stop, dry);
     default: return hipErrorInvalidValue;
   }
 }

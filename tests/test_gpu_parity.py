@@ -72,6 +72,9 @@ SMALL_BF16 = [
     # 128-row state blocks (310 rows against 80 tiles: one tile per range with three blocks, two with four)
     ("bf16_b31_mid_k2", 128, 320, 20300, 3, (5, 2, 2), 6, 31),    # 31, 155, 310
     ("bf16_b31_mid_k3", 128, 320, 20300, 3, (5, 2, 3), 6, 31),
+    # the same block heights with full 256-row tiles and two tiles per range (the cases above get short tiles)
+    ("bf16_b31_mid_two_tiles", 64, 128, 36000, 3, (5, 2, 2), 6, 31),        # 310 rows, 141 tiles over 85 ranges
+    ("bf16_b31_tall_two_tiles", 64, 128, 21400, 4, (5, 3, 2, 2), 6, 31),    # 930 rows, 84 tiles over 42 ranges
     # first projection split along K (long E, more than 16 rows): four parts, and two parts with two row blocks
     ("bf16_b20_long_e", 2048, 64, 300, 2, (2, 2), 4, 20),
     ("bf16_b40_long_e", 1024, 128, 300, 2, (3, 2), 6, 40),
