@@ -112,7 +112,8 @@ void spec_destroy(spec_model_t* m);
  * for every node of depth i-1, takes the top_k[i] most likely tokens of
  * log_softmax(Head_i state_i) as that node's children, and after n stages keeps
  * the B leaves with the largest summed log-probability.
- *   state     dev [batch, E] weight_dtype      base model's last hidden vector
+ *   state     dev [batch, E] weight_dtype      base model's last hidden vector; rows contiguous,
+ *                                              16-byte aligned (SPEC_EINVAL otherwise)
  *   last_tok  dev [batch] int32 in [0, V)      token the base model just sampled
  *   top_k     host [n_predict]                 1 <= top_k[i] <= max_top_k[i], <= V
  *   B                                          1 <= B <= prod(top_k) <= SPEC_MAX_LEAVES
@@ -151,7 +152,7 @@ spec_status_t spec_verify(const void* base_logits, int32_t logits_dtype, const i
 
 /* Parity aid: full log-softmax rows of stage `stage`'s head for given states,
  * computed by the same contraction kernels as spec_draft with a store epilogue.
- *   states dev [rows, D] weight_dtype;  logp dev [rows, V] float32;  rows <= max rows of the model. */
+ *   states dev [rows, D] weight_dtype, 16-byte aligned;  logp dev [rows, V] float32;  rows <= max rows of the model. */
 spec_status_t spec_head_logp(spec_model_t* m, int32_t stage, const void* states, int32_t rows,
                              float* logp, void* hip_stream);
 

@@ -158,7 +158,8 @@ struct GemmArgs {
   int64_t ldo[2];
   int mode0;          // matrix 0: 0 = top-k partials, 1 = store.  Matrix 1 always stores.
   int kt;
-  const u32x4* b;     // packed states
+  const u32x4* b;     // states: packed tiles, or (narrow kernel only) row-major bf16 [R][b_ld] if b_rowmajor
+  int b_rowmajor, b_ld;
   int R, mt_total;
   int m_tiles, n_ranges, chunk;  // chunk = workgroups per XCD
   int ts;                        // 16-row weight tiles per workgroup tile (wide kernel)
@@ -204,7 +205,15 @@ __global__ __launch_bounds__(256, (MI <= 4 ? 2 : 1)) void head_gemm_kernel(GemmA
     const int i = s * 256 + tid;
     const int mtl = i / (KS * 64), rem = i % (KS * 64);
     const int mt = min(mtile * MI + mtl, p.mt_total - 1);
-    sptr[s] = p.b + (int64_t)mt * kt * 64 + (int64_t)slab0 * KS * 64 + rem;
+    if (p.b_rowmajor) {
+      // gather the slot from the caller's row-major rows: slot (K step ts, lane l) of a 16-row tile holds
+      // row l % 16, columns 32 ts + 8 (l / 16) .. + 8; a slab further on is KS * 32 columns = KS * 4 slots
+      const int ts = rem >> 6, l = rem & 63;
+      const int row = min(mt * 16 + (l & 15), p.R - 1);   // rows past R are masked in the epilogue
+      sptr[s] = p.b + ((int64_t)row * p.b_ld + ((int64_t)slab0 * KS + ts) * 32 + (l >> 4) * 8) / 8;
+    } else {
+      sptr[s] = p.b + (int64_t)mt * kt * 64 + (int64_t)slab0 * KS * 64 + rem;
+    }
   }
 
   // weight fragment pointers of this wave for a given tile of the list
@@ -223,7 +232,7 @@ __global__ __launch_bounds__(256, (MI <= 4 ? 2 : 1)) void head_gemm_kernel(GemmA
   // Rotating register sets: weight fragments a[], state slots g[].
   u32x4 a[NSET][NI][KS], g[NSET][SPT];
   auto load_g = [&](u32x4 (&gs)[SPT], int sl) {
-    const int64_t off = (int64_t)sl * KS * 64;
+    const int64_t off = (int64_t)sl * KS * (p.b_rowmajor ? 4 : 64);
 #pragma unroll
     for (int s = 0; s < SPT; ++s) gs[s] = sptr[s][off];
   };
@@ -911,6 +920,9 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
   if (nm == 0) return hipErrorInvalidValue;
   a.kt = job.kt;
   a.b = static_cast<const u32x4*>(job.b_src);
+  a.b_rowmajor = job.b_rowmajor;
+  a.b_ld = job.b_ld;
+  if (job.b_rowmajor && (pl.ni != 1 || (job.b_ld & 7))) return hipErrorInvalidValue;  // narrow kernel only
   a.R = job.R;
   a.mt_total = (job.R + 15) / 16;
   a.m_tiles = pl.m_tiles;

@@ -496,13 +496,13 @@ static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, c
     HIP_TRY(launch_head_skinny(job, m->n_cu, st, EV0(slot), EV1(slot)));
     return SPEC_OK;
   }
-  // general path wants tiled states
-  if (b_rowmajor) {
+  GemmPlan pl = plan_gemm(R, k_top, job.n_head, job.n_proj, job.kt, m->n_cu);
+  // the wide kernel wants tiled states; the narrow one gathers row-major rows itself
+  if (b_rowmajor && pl.ni != 1) {
     HIP_TRY(launch_pack_bf16(b_src, m->state_in, R, K, false, st));
     job.b_src = m->state_in;
     job.b_rowmajor = 0;
   }
-  GemmPlan pl = plan_gemm(R, k_top, job.n_head, job.n_proj, job.kt, m->n_cu);
   if (pl.ksplit > 1) {
     if (!proj_parts) pl.ksplit = 1;  // the caller reads out_proj as it is
     else job.proj_part_stride = (int64_t)R * job.ld_proj;
@@ -524,6 +524,7 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
   if (!state || !last_tok || !top_k || !cand_tokens || !cand_scores || !cand_leaf)
     return fail(SPEC_EINVAL, "a required pointer is NULL");
   if (batch < 1) return fail(SPEC_EINVAL, "batch = %d must be >= 1", batch);
+  if (reinterpret_cast<uintptr_t>(state) & 15) return fail(SPEC_EINVAL, "state must be 16-byte aligned");
   if (batch > m->cfg.max_batch) return fail(SPEC_ESHAPE, "batch = %d exceeds max_batch = %d", batch, m->cfg.max_batch);
   const int n = m->cfg.n_predict, E = m->cfg.emb_dim, D = m->cfg.inner_dim, V = m->cfg.vocab;
   int64_t L = 1;
@@ -715,6 +716,7 @@ extern "C" spec_status_t spec_head_logp(spec_model_t* m, int32_t stage, const vo
   if (!m) return fail(SPEC_EINVAL, "model is NULL");
   if (!states || !logp) return fail(SPEC_EINVAL, "a required pointer is NULL");
   if (stage < 0 || stage >= m->cfg.n_predict) return fail(SPEC_EINVAL, "stage = %d out of range", stage);
+  if (reinterpret_cast<uintptr_t>(states) & 15) return fail(SPEC_EINVAL, "states must be 16-byte aligned");
   if (rows < 1 || rows > m->max_rows) return fail(SPEC_ESHAPE, "rows = %d outside [1, %lld]", rows, (long long)m->max_rows);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int D = m->cfg.inner_dim, V = m->cfg.vocab;

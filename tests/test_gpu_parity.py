@@ -419,6 +419,12 @@ def test_runtime_argument_errors():
         B.spec_draft(step.model, state.cuda(), last.cuda(), wl.top_k, 5, step.cand_tokens, step.cand_scores,
                      step.cand_leaf)
     assert e.value.status == B.SPEC_EINVAL
+    # a state that does not start on a 16-byte boundary (a view shifted by one bf16 element)
+    shifted = torch.zeros(wl.batch * wl.emb_dim + 8, dtype=torch.bfloat16, device="cuda")[1:1 + wl.batch * wl.emb_dim]
+    with pytest.raises(B.SpecError) as e:
+        B.spec_draft(step.model, shifted.view(wl.batch, wl.emb_dim), last.cuda(), wl.top_k, wl.B, step.cand_tokens,
+                     step.cand_scores, step.cand_leaf)
+    assert e.value.status == B.SPEC_EINVAL
     # the model still works after rejected calls
     step.draft(state.cuda(), last.cuda())
     torch.cuda.synchronize()
