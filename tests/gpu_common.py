@@ -61,38 +61,58 @@ def run_workload(wl: W.Workload, ln_affine: str = "identity", gen_device: str = 
 
     seqs = list(range(wl.batch)) if sample_seqs is None else list(sample_seqs)
     wn = W.weights_to_numpy(w)
-    st_np = W.to_numpy_f32(state)[seqs]
-    lt_np = last.cpu().numpy()[seqs]
+    # (the contraction operands once in float64, so that the oracle's matmuls do not convert them per call)
+    wn["head"] = [a.astype(np.float64) for a in wn["head"]]
+    wn["proj"] = [a.astype(np.float64) for a in wn["proj"]]
+    st_np = W.to_numpy_f32(state)
+    lt_np = last.cpu().numpy()
     ms, me, eps = step.model.scalars()
     ows, owe = (None, None) if w_s < 0 else (w_s, w_e)
-    t1 = time.time()
-    od = O.draft(wn, st_np, lt_np, wl.top_k, wl.B, w_s=ows, w_e=owe, state_dtype=wl.weight_dtype, keep_logits=True)
-    log("  oracle draft on %d sequence(s) done (%.1fs)" % (len(seqs), time.time() - t1))
     if w_s < 0:
         want = O.mix_weights(wl.n_predict)
         assert abs(ms - want[0]) < 1e-6 and abs(me - want[1]) < 1e-6 and abs(eps - 1e-5) < 1e-12
 
-    def along(q, path):
-        return O.logp_along_path(wn, st_np[q], int(lt_np[q]), path, wl.n_predict, w_s=ows, w_e=owe,
-                                 state_dtype=wl.weight_dtype)
+    # the oracle runs the compared sequences in chunks that keep its float64 logit rows bounded (~1.5 GB)
+    rows_per_seq = sum(wl.rows()) // wl.batch
+    chunk = max(1, min(len(seqs), int(1.5e9 // (8 * rows_per_seq * wl.vocab))))
+    rep = parity.Report()
+    parts = []
+    t1 = time.time()
+    for c0 in range(0, len(seqs), chunk):
+        sub = seqs[c0:c0 + chunk]
+        od_c = O.draft(wn, st_np[sub], lt_np[sub], wl.top_k, wl.B, w_s=ows, w_e=owe, state_dtype=wl.weight_dtype,
+                       keep_logits=True)
 
-    rep = parity.compare_draft(od, gt, gc, wl.top_k, wl.batch, seq_index=seqs, along_path=along)
-    log("  draft parity: " + rep.line())
+        def along(q, path, sub=sub):
+            return O.logp_along_path(wn, st_np[sub[q]], int(lt_np[sub[q]]), path, wl.n_predict, w_s=ows, w_e=owe,
+                                     state_dtype=wl.weight_dtype)
+
+        rep.merge(parity.compare_draft(od_c, gt, gc, wl.top_k, wn["head"], seq_index=sub, along_path=along))
+        od_c.logits, od_c.states = [], []
+        parts.append(od_c)
+        log("  oracle draft + comparison of sequences %d..%d done (%.1fs)" % (sub[0], sub[-1], time.time() - t1))
+    od = O.DraftResult(*[np.concatenate([getattr(p, name) for p in parts]) for name in
+                         ("cand_tokens", "cand_scores", "cand_leaf", "leaf_tokens", "leaf_scores")])
+    assert rep.seqs == len(seqs)
+    log("  draft parity (%d of %d sequences): %s" % (len(seqs), wl.batch, rep.line()))
     for note in rep.notes[:5]:
         log("    " + note)
 
     # The debug outputs above are not free of side effects on the launch sequence (with them the first
     # stage always gets a launch of its own): the configuration the benchmark times is the one WITHOUT
-    # them, and it must produce the same candidates (same tokens; scores up to the order of two block sums).
+    # them.  It must choose the same candidates, and its scores are held to the oracle's leaf scores.
     if fused is None and w_s < 0 and not tied:
         plain = Step(wl, w_dev)
         plain.draft(state_d, last_d)
         torch.cuda.synchronize()
         assert torch.equal(plain.cand_tokens, step.cand_tokens), "candidates differ between debug and plain run"
         assert torch.equal(plain.cand_leaf, step.cand_leaf)
-        assert (plain.cand_scores - step.cand_scores).abs().max().item() < 2e-3
+        p_sc, p_leaf = plain.cand_scores.cpu().numpy().astype(np.float64), plain.cand_leaf.cpu().numpy()
+        for g in seqs:
+            d = np.abs(p_sc[g] - rep.ref_scores[g][p_leaf[g]]).max()
+            assert d <= parity.abs_score(wl.n_predict), "plain run, seq %d: leaf scores off by %.2e from the oracle's" % (g, d)
         plain.close()
-        log("  plain (benchmark) configuration reproduces the candidates")
+        log("  plain (benchmark) configuration: same candidates, scores within the bar of the oracle's")
 
     ov = None
     if check_verify:

@@ -6,13 +6,21 @@ accepted lengths bit-exact, except where the oracle's competing logits (or leaf
 scores) differ by less than 1e-3; stage states and log-probabilities within a
 maximum relative error of 2e-2.
 
-A stage state is rounded to bf16 from float32 arithmetic on the device and from
-float64 arithmetic in the oracle; a value close to a rounding boundary lands on
-the other side in about one element in a thousand, which moves the logits of
-that row by up to a few 1e-3.  So the band inside which a different choice is
-accepted is 1e-3 plus the deviation actually measured between the two sides'
-values for the competing entries, and those deviations are themselves held to
-an absolute cap (ABS_LOGP, ABS_SCORE) far inside the 2e-2 relative bar.
+How a differing choice is judged.  The only place where the two sides start from
+different numbers is a stage state: it is rounded to bf16 from float32 arithmetic
+on the device and from float64 arithmetic in the oracle, and about one element in
+a thousand lands on the other side of a rounding boundary.  States are therefore
+held to the 2e-2 bar.  Everything downstream of a state row (logits, log-sum-exp,
+log-probabilities, top-k, leaf scores, top-B) is then judged ON THE SAME INPUT:
+the oracle's head is evaluated on the device's own state row, and against that
+  * the device's log-sum-exp and log-probabilities must agree to SAME_INPUT
+    (only float32 versus float64 accumulation separates them),
+  * a set of tokens (or of leaves) that differs from the oracle's must be a valid
+    choice inside the strict TIE = 1e-3 band, with no allowance for the device's
+    own deviation.
+The deviation from the oracle's OWN rows (oracle state, oracle logits) is capped
+separately (ABS_LOGP, ABS_SCORE: what is observed, times a stated margin) and
+reported.
 
 Relative error of a tensor = max|gpu - oracle| / max|oracle|; in addition every
 element must satisfy |gpu - oracle| <= 2e-2 * |oracle| + 2e-2 * rms(oracle)
@@ -29,29 +37,54 @@ from oracle import spec_oracle as O
 
 TIE = 1e-3
 REL = 2e-2
-ABS_LOGP = 1e-2      # cap on |log-prob(gpu) - log-prob(oracle)| of a chosen token
-ABS_SCORE = 2e-2     # cap on the deviation of a leaf score (sum of up to 8 log-probs)
+# device value against the oracle's head evaluated on the device's own state row: products of two
+# bf16 values are exact in float32, so what is left is the rounding of up to 8192 float32 additions
+# of O(1) partial sums (sqrt(8192) * 2^-24 ~ 5e-6, worst case 5e-4) and the float32 exp / log of the
+# running softmax.  Observed on MI355X: <= 2e-5.
+SAME_INPUT = 2e-4
+# device log-probability against the oracle's OWN row (oracle state): a flipped bf16 state element
+# moves a logit by |h| * ulp ~ 0.02 * 0.008 = 1.6e-4; a row has a handful of flips.  Observed over all
+# configurations <= 1e-3; cap = 3 x that.
+ABS_LOGP = 3e-3
+
+
+def abs_score(n: int) -> float:
+    """Cap on the deviation of a leaf score (a sum of n log-probabilities) from the oracle's own."""
+    return n * ABS_LOGP
 
 
 @dataclass
 class Report:
     rows_checked: int = 0
     rows_exact: int = 0
-    rows_exempt: int = 0          # differ from the oracle only inside the 1e-3 band
-    rows_skipped_below_exempt: int = 0
-    cand_exempt: int = 0
+    rows_exempt: int = 0          # differ from the oracle's tokens, valid inside the strict 1e-3 band
+    rows_skipped_below_exempt: int = 0   # rows under an exempt row: judged along the device's path
+    cand_exempt: int = 0          # candidate slots that differ from the oracle's, valid inside the band
+    seqs_cand_identical: int = 0  # sequences whose candidates equal the oracle's own bit for bit
+    seqs: int = 0
     max_state_rel: float = 0.0
-    max_logp_abs: float = 0.0
+    max_logp_abs: float = 0.0     # against the oracle's own rows
     max_lse_abs: float = 0.0
     max_score_abs: float = 0.0
+    max_same_input_abs: float = 0.0   # against the oracle's head on the device's state rows
     notes: List[str] = field(default_factory=list)
+    ref_scores: dict = field(default_factory=dict)   # g -> float64 [L]: leaf scores a plain launch is held to
 
     def line(self) -> str:
-        return ("rows %d exact %d exempt %d skipped %d | cand exempt %d | state rel %.2e logp abs %.2e "
-                "lse abs %.2e score abs %.2e" % (self.rows_checked, self.rows_exact, self.rows_exempt,
-                                                 self.rows_skipped_below_exempt, self.cand_exempt,
-                                                 self.max_state_rel, self.max_logp_abs, self.max_lse_abs,
-                                                 self.max_score_abs))
+        return ("rows %d exact %d exempt %d below-exempt %d | cand identical %d/%d seqs, exempt slots %d | "
+                "state rel %.2e | vs oracle rows: logp %.2e lse %.2e score %.2e | same input: %.2e"
+                % (self.rows_checked, self.rows_exact, self.rows_exempt, self.rows_skipped_below_exempt,
+                   self.seqs_cand_identical, self.seqs, self.cand_exempt, self.max_state_rel, self.max_logp_abs,
+                   self.max_lse_abs, self.max_score_abs, self.max_same_input_abs))
+
+    def merge(self, o: "Report") -> None:
+        for name in ("rows_checked", "rows_exact", "rows_exempt", "rows_skipped_below_exempt", "cand_exempt",
+                     "seqs_cand_identical", "seqs"):
+            setattr(self, name, getattr(self, name) + getattr(o, name))
+        for name in ("max_state_rel", "max_logp_abs", "max_lse_abs", "max_score_abs", "max_same_input_abs"):
+            setattr(self, name, max(getattr(self, name), getattr(o, name)))
+        self.notes.extend(o.notes)
+        self.ref_scores.update(o.ref_scores)
 
 
 def rel_err(got: np.ndarray, want: np.ndarray) -> float:
@@ -72,99 +105,117 @@ def assert_close_tensor(got: np.ndarray, want: np.ndarray, what: str) -> float:
     return r
 
 
-def _row_valid_in_band(logits_row: np.ndarray, chosen: Sequence[int], k: int, dev: float = 0.0) -> bool:
-    """GPU's chosen tokens are an acceptable top-k of the oracle's row: each one
-    within the band of the k-th best, in an order that descends within the band.
-    dev = measured deviation of the GPU's values on this row."""
-    band = TIE + 2.0 * dev
-    kth = np.sort(logits_row)[-k]
-    vals = logits_row[np.asarray(chosen)]
+def valid_choice_in_band(values: np.ndarray, chosen: Sequence[int], band: float = TIE) -> bool:
+    """`chosen` (k distinct indices, in the order they were emitted) is an acceptable
+    "k largest, descending" of `values`: every chosen value within `band` of the k-th
+    largest, and the order descends within `band`."""
+    k = len(chosen)
     if len(set(int(c) for c in chosen)) != k:
         return False
+    kth = np.partition(values, len(values) - k)[len(values) - k]
+    vals = values[np.asarray(chosen)]
     if np.any(vals < kth - band):
         return False
     return bool(np.all(np.diff(vals) <= band))
 
 
-def _check_row_along_path(along_path, gpu_tables, top_k, per_seq, i, q, g, rl, rep):
-    # tokens chosen by the ancestors of row rl of stage i (GPU tables)
-    path, r = [], rl
-    for d in range(i, 0, -1):
-        parent, rank = r // top_k[d - 1], r % top_k[d - 1]
-        path.append(int(gpu_tables["tok"][d - 1][g * per_seq[d - 1] + parent][rank]))
-        r = parent
-    path.reverse()
-    s_o, lp_o = along_path(q, path)
-    rg = g * per_seq[i] + rl
-    assert_close_tensor(gpu_tables["states"][i][rg], s_o, "state along path, stage %d row %d" % (i, rg))
-    t_g = gpu_tables["tok"][i][rg]
-    d = np.abs(gpu_tables["logp"][i][rg].astype(np.float64) - lp_o[t_g])
-    assert np.all(d <= ABS_LOGP)
-    assert _row_valid_in_band(lp_o, t_g, top_k[i], float(d.max())), (
-        "stage %d row %d below a near-tie: tokens not a valid top-k" % (i, rg))
+def _judge_row(rep: Report, what: str, k: int, tok_g, logp_g, lse_g, lp_same, lse_same, lp_own, tok_own) -> bool:
+    """One head row of the device.  lp_same / lse_same: the oracle's head on the device's own state
+    row; lp_own: the oracle's row from the oracle's state (its own, or followed along the device's
+    path); tok_own: the oracle's top-k of that row.  Returns True when the tokens equal tok_own."""
+    d_same = max(abs(float(lse_g) - float(lse_same)),
+                 float(np.abs(logp_g.astype(np.float64) - lp_same[tok_g]).max()))
+    rep.max_same_input_abs = max(rep.max_same_input_abs, d_same)
+    assert d_same <= SAME_INPUT, "%s: log-probabilities / lse off by %.2e from the oracle's head on the same state" % (what, d_same)
+    d_own = float(np.abs(logp_g.astype(np.float64) - lp_own[tok_g]).max())
+    rep.max_logp_abs = max(rep.max_logp_abs, d_own)
+    assert d_own <= ABS_LOGP, "%s: log-probabilities off by %.2e from the oracle's row" % (what, d_own)
+    if np.array_equal(tok_own, tok_g):
+        return True
+    assert valid_choice_in_band(lp_same, tok_g), (
+        "%s: tokens %s vs oracle %s are not a top-%d of the oracle's logits on the same state inside the %.0e band"
+        % (what, tok_g.tolist(), np.asarray(tok_own).tolist(), k, TIE))
+    return False
 
 
 def compare_draft(oracle_res: O.DraftResult, gpu_tables: dict, gpu_cand: dict, top_k: Sequence[int],
-                  batch: int, seq_index: Optional[Sequence[int]] = None, along_path=None) -> Report:
+                  heads: Sequence[np.ndarray], seq_index: Optional[Sequence[int]] = None,
+                  along_path=None) -> Report:
     """oracle_res must have been computed with keep_logits=True for the same
     inputs.  gpu_tables: per-stage lists 'states', 'tok', 'logp', 'lse' (numpy).
     gpu_cand: 'tokens' [b,B,n], 'scores' [b,B], 'leaf' [b,B].
+    heads: the per-stage head matrices [V, D] (numpy), for the oracle's head on the device's state rows.
     seq_index: if the oracle only ran a subset of the sequences, their indices in
     the GPU batch (oracle row q corresponds to GPU sequence seq_index[q]).
     along_path(q, path_tokens) -> (state, logp_row): the oracle followed along a
-    path the GPU chose (O.logp_along_path bound to the inputs); used to judge
-    the rows below a near-tie, whose positions no longer line up with the oracle's
-    own tree.  Without it such rows are only counted."""
+    path the GPU chose (O.logp_along_path bound to the inputs); judges the rows
+    below an exempt row, whose positions no longer line up with the oracle's own tree."""
     rep = Report()
     n = len(top_k)
     ob = oracle_res.cand_tokens.shape[0]
     seq_index = list(range(ob)) if seq_index is None else list(seq_index)
     assert len(seq_index) == ob
+    rep.seqs = ob
 
-    # rows of stage i for oracle sequence q / gpu sequence g
-    per_seq = [1]
+    per_seq = [1]                      # rows of stage i per sequence
     for k in top_k[:-1]:
         per_seq.append(per_seq[-1] * k)
 
     tree_identical = [True] * ob
-    _exempt, _skipped = set(), set()
+    lp_same_tabs = [[None] * n for _ in range(ob)]    # [q][i] -> float64 [per_seq[i], k_i]: oracle-on-device-state logp of the device's tokens
+    _exempt, _below = set(), set()
     for i in range(n):
         k = top_k[i]
+        # the oracle's head on the device's state rows of this stage, for the compared sequences
+        rows_g = np.concatenate([np.arange(g * per_seq[i], (g + 1) * per_seq[i]) for g in seq_index])
+        lp_same_all, lse_same_all = O.log_softmax(O.head_logits(gpu_tables["states"][i][rows_g], heads[i]))
         for q, g in enumerate(seq_index):
-            # rows whose ancestors all agree are comparable position by position
+            lp_same_tabs[q][i] = np.empty((per_seq[i], k), np.float64)
             for rl in range(per_seq[i]):
-                ro, rg = q * per_seq[i] + rl, g * per_seq[i] + rl
+                ro, rg, rs = q * per_seq[i] + rl, g * per_seq[i] + rl, q * per_seq[i] + rl
+                tok_g, logp_g, lse_g = gpu_tables["tok"][i][rg], gpu_tables["logp"][i][rg], gpu_tables["lse"][i][rg]
+                lp_same_tabs[q][i][rl] = lp_same_all[rs][tok_g]
+                below = False
                 if i > 0:
                     parent = rl // top_k[i - 1]
-                    if (i - 1, q, parent) in _exempt or (i - 1, q, parent) in _skipped:
-                        _skipped.add((i, q, rl))
-                        rep.rows_skipped_below_exempt += 1
-                        if along_path is not None:
-                            _check_row_along_path(along_path, gpu_tables, top_k, per_seq, i, q, g, rl, rep)
-                        continue
-                rep.rows_checked += 1
-                s_o, s_g = oracle_res.states[i][ro], gpu_tables["states"][i][rg]
-                rep.max_state_rel = max(rep.max_state_rel, assert_close_tensor(s_g, s_o, "state stage %d row %d" % (i, rg)))
-                lse_d = abs(float(gpu_tables["lse"][i][rg]) - float(oracle_res.row_lse[i][ro]))
-                rep.max_lse_abs = max(rep.max_lse_abs, lse_d)
-                assert lse_d <= REL * max(1.0, abs(float(oracle_res.row_lse[i][ro]))), "lse stage %d row %d" % (i, rg)
-                t_o, t_g = oracle_res.topk_tok[i][ro], gpu_tables["tok"][i][rg]
-                # log-probabilities of the GPU's tokens against the oracle's full row
-                logit_row = oracle_res.logits[i][ro]
-                lp_row_o = logit_row - oracle_res.row_lse[i][ro]
-                d = np.abs(gpu_tables["logp"][i][rg].astype(np.float64) - lp_row_o[t_g])
-                rep.max_logp_abs = max(rep.max_logp_abs, float(d.max()))
-                assert np.all(d <= ABS_LOGP), "logp stage %d row %d: %s" % (i, rg, d)
-                if np.array_equal(t_o, t_g):
+                    below = (i - 1, q, parent) in _exempt or (i - 1, q, parent) in _below
+                what = "stage %d seq %d row %d" % (i, g, rl)
+                if below:
+                    # the oracle's own tree has other tokens above this row: follow the device's path
+                    _below.add((i, q, rl))
+                    rep.rows_skipped_below_exempt += 1
+                    assert along_path is not None, "rows below an exempt row need along_path"
+                    path, r = [], rl
+                    for d in range(i, 0, -1):
+                        par, rank = r // top_k[d - 1], r % top_k[d - 1]
+                        path.append(int(gpu_tables["tok"][d - 1][g * per_seq[d - 1] + par][rank]))
+                        r = par
+                    path.reverse()
+                    s_o, lp_o = along_path(q, path)
+                    tok_o = O.topk_desc(lp_o.astype(np.float32), k)
+                    lse_o = None
+                else:
+                    rep.rows_checked += 1
+                    s_o = oracle_res.states[i][ro]
+                    lp_o = oracle_res.logits[i][ro] - oracle_res.row_lse[i][ro]
+                    tok_o = oracle_res.topk_tok[i][ro]
+                    lse_o = float(oracle_res.row_lse[i][ro])
+                rep.max_state_rel = max(rep.max_state_rel,
+                                        assert_close_tensor(gpu_tables["states"][i][rg], s_o, "state " + what))
+                if lse_o is not None:
+                    lse_d = abs(float(lse_g) - lse_o)
+                    rep.max_lse_abs = max(rep.max_lse_abs, lse_d)
+                    assert lse_d <= ABS_LOGP, "lse %s off by %.2e" % (what, lse_d)
+                same = _judge_row(rep, what, k, tok_g, logp_g, lse_g, lp_same_all[rs], lse_same_all[rs], lp_o, tok_o)
+                if below:
+                    continue
+                if same:
                     rep.rows_exact += 1
                 else:
-                    assert _row_valid_in_band(logit_row, t_g, k, float(d.max())), (
-                        "stage %d row %d: tokens %s vs oracle %s differ outside the %.0e band"
-                        % (i, rg, t_g.tolist(), t_o.tolist(), TIE))
                     rep.rows_exempt += 1
                     _exempt.add((i, q, rl))
                     tree_identical[q] = False
-                    rep.notes.append("stage %d seq %d row %d: near-tie %s vs %s" % (i, g, rl, t_g.tolist(), t_o.tolist()))
+                    rep.notes.append("stage %d seq %d row %d: near-tie %s vs %s" % (i, g, rl, tok_g.tolist(), tok_o.tolist()))
 
     # tree expansion + pruning: a pure function of the per-stage tables, so the GPU's
     # candidates must equal the oracle's expand/prune applied to the GPU's own tables.
@@ -174,29 +225,31 @@ def compare_draft(oracle_res: O.DraftResult, gpu_tables: dict, gpu_cand: dict, t
         tabs_lp = [gpu_tables["logp"][i][g * per_seq[i]:(g + 1) * per_seq[i]] for i in range(n)]
         leaf_tokens, leaf_scores = O.expand_tree(tabs_tok, tabs_lp, top_k, 1)
         c_tok, c_sc, c_leaf = O.prune(leaf_tokens, leaf_scores, B)
-        assert np.array_equal(gpu_cand["leaf"][g], c_leaf[0]), "seq %d: cand_leaf differs from expand/prune of its own tables" % g
+        lg = gpu_cand["leaf"][g]
+        assert np.array_equal(lg, c_leaf[0]), "seq %d: cand_leaf differs from expand/prune of its own tables" % g
         assert np.array_equal(gpu_cand["tokens"][g], c_tok[0]), "seq %d: cand_tokens" % g
         assert np.array_equal(gpu_cand["scores"][g], c_sc[0]), "seq %d: cand_scores not bit-equal to the fp32 stage-order sum" % g
-        # and against the oracle's own candidates, where the trees are the same
+        # the same choice judged on the same input: leaf scores from the oracle's head on the device's states
+        _, sc_same = O.expand_tree(tabs_tok, [t.astype(np.float32) for t in lp_same_tabs[q]], top_k, 1)
+        sc_same = sc_same[0].astype(np.float64)
+        rep.ref_scores[g] = sc_same
+        d = float(np.abs(gpu_cand["scores"][g].astype(np.float64) - sc_same[lg]).max())
+        rep.max_same_input_abs = max(rep.max_same_input_abs, d)
+        assert d <= n * SAME_INPUT, "seq %d: leaf scores off by %.2e from the oracle's on the same states" % (g, d)
+        assert valid_choice_in_band(sc_same, lg), "seq %d: candidates are not a top-%d of the leaf scores inside the band" % (g, B)
         if tree_identical[q]:
+            # against the oracle's own candidates
             sc_o = oracle_res.leaf_scores[q].astype(np.float64)
-            d = np.abs(gpu_cand["scores"][g].astype(np.float64) - sc_o[gpu_cand["leaf"][g]])
-            rep.max_score_abs = max(rep.max_score_abs, float(d.max()))
-            # a score is a sum of n log-probabilities, each held to the relative bar
-            assert d.max() <= ABS_SCORE, "seq %d: leaf scores differ by %.2e | %s" % (g, d.max(), rep.line())
-            dev = np.abs(leaf_scores[0].astype(np.float64) - sc_o)          # per leaf, all leaves
-            lo, lg = oracle_res.cand_leaf[q], gpu_cand["leaf"][g]
-            if not np.array_equal(lo, lg):
-                for c in range(B):
-                    if lo[c] != lg[c]:
-                        assert abs(sc_o[lo[c]] - sc_o[lg[c]]) < TIE + dev[lo[c]] + dev[lg[c]], (
-                            "seq %d cand %d: leaf %d vs oracle %d outside the band (oracle scores %.6f vs %.6f) | %s"
-                            % (g, c, lg[c], lo[c], sc_o[lg[c]], sc_o[lo[c]], rep.line()))
-                        rep.cand_exempt += 1
-                cut = sc_o[lo[-1]]
-                for leaf in set(lo.tolist()) ^ set(lg.tolist()):
-                    assert abs(sc_o[leaf] - cut) < TIE + dev[leaf] + dev[lo[-1]]
-            else:
+            d = float(np.abs(gpu_cand["scores"][g].astype(np.float64) - sc_o[lg]).max())
+            rep.max_score_abs = max(rep.max_score_abs, d)
+            assert d <= abs_score(n), "seq %d: leaf scores differ by %.2e from the oracle's | %s" % (g, d, rep.line())
+            rep.ref_scores[g] = sc_o
+            lo = oracle_res.cand_leaf[q]
+            if np.array_equal(lo, lg):
                 assert np.array_equal(oracle_res.cand_tokens[q], gpu_cand["tokens"][g])
+                rep.seqs_cand_identical += 1
+            else:
+                rep.cand_exempt += int((lo != lg).sum())
+                rep.notes.append("seq %d: candidate order / cut differs from the oracle's in %d slots (valid inside the band)"
+                                 % (g, int((lo != lg).sum())))
     return rep
-
