@@ -8,6 +8,13 @@ stream, on one batch of seeded synthetic inputs that are resident in HBM before
 the timed region starts (the base model's forward between the two calls is not
 part of this path; its logits are pre-generated).  Prints ONE JSON line.
 
+The metric is quoted at batch 1 and at batch 64.  `value`, `config`, `roofline`
+and `cpu_baseline` are those of the batch-1 workload (`llama7b_b1`, bound by HBM
+bandwidth); with the default workload the line also carries a `batch64` object:
+the same measurement of `llama7b_b64` (bound by the matrix cores), with its own
+`roofline` for the dominant dense kernel and the fraction of the bf16 MFMA peak
+the whole draft reaches.
+
 Extra objects on the line:
   roofline      dominant contraction kernel: algorithmic bytes (or flops) per
                 launch / its average launch duration, measured live with HIP
@@ -19,6 +26,7 @@ Extra objects on the line:
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -39,53 +47,32 @@ def kernel_name(kid: int) -> str:
             4: "draft_fused_kernel"}[kid]
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="llama7b_b1")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0)
-    ap.add_argument("--verbose", action="store_true", help="per-shape timing of the contraction launches on stderr")
-    ap.add_argument("--fused", action="store_true",
-                    help="run the draft as one fused launch (spec_set_fused) instead of separate launches")
-    ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
-                    help="instead of the benchmark: launch the library's plain copy kernel over BYTES a few times "
-                         "(calibration of rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding in "
-              "this path)" % args.gpus, file=sys.stderr)
-        return 2
+def kernel_sources_digest() -> str:
+    """Digest of the library's kernel sources: a stored counter measurement belongs to the
+    kernels it was taken on, and is dropped once they change."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2404_19124_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
 
-    import numpy as np
+
+def measure(wl_name: str, steps: int, warmup: int, verbose: bool = False, fused: bool = False):
+    """Times `steps` whole steps of one workload, then the same number again with the library's
+    per-launch events on, and the draft and the verify alone.  Returns (metrics dict, context for
+    the CPU baseline)."""
     import torch
     from paper_2404_19124_amd import binding as B
     from paper_2404_19124_amd import workloads as W
     from paper_2404_19124_amd.runner import Step
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-    torch.cuda.set_device(0)
-    if args.copy_probe:
-        n = args.copy_probe // 16 * 16
-        src = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
-        dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
-        torch.cuda.synchronize()
-        for _ in range(5):
-            B.spec_copy_probe(src, dst, torch.cuda.current_stream())
-        torch.cuda.synchronize()
-        ok = bool(torch.equal(src, dst))
-        print(json.dumps({"copy_probe_bytes": n, "launches": 5, "copied_correctly": ok}), flush=True)
-        return 0 if ok else 1
-    wl = W.WORKLOADS[args.workload]
+    wl = W.WORKLOADS[wl_name]
     gen = W.make_generator(wl.seed, "cuda")
     w = W.make_speculator(wl, gen, device="cuda")
     state, last = W.make_draft_inputs(wl, gen, device="cuda")
     step = Step(wl, w)
-    if args.fused:
+    if fused:
         B.spec_set_fused(step.model, True)
     stream = torch.cuda.current_stream()
 
@@ -99,27 +86,27 @@ def main() -> int:
         step.draft(state, last, stream)
         step.verify(logits, None, stream)
 
-    for _ in range(args.warmup):
+    def timed(fn, reps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    for _ in range(warmup):
         one_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / args.steps
-    steps_per_s = args.steps / dt
+    dt = timed(one_step, steps)
+    ms_per_step = dt * 1e3 / steps
+    steps_per_s = steps / dt
     mean_accept = float(step.accept_len.float().mean())
+    ms_draft = timed(lambda: step.draft(state, last, stream), steps) * 1e3 / steps
+    ms_verify = timed(lambda: step.verify(logits, None, stream), steps) * 1e3 / steps
 
     # ---- dominant kernel, timed live with events around each launch
-    B.spec_profile_enable(step.model, 16 * args.steps)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step()
-    torch.cuda.synchronize()
-    ms_per_step_events = (time.perf_counter() - t1) * 1e3 / args.steps
-    recs = B.spec_profile_read(step.model, 16 * args.steps)
+    B.spec_profile_enable(step.model, 16 * steps)
+    ms_per_step_events = timed(one_step, steps) * 1e3 / steps
+    recs = B.spec_profile_read(step.model, 16 * steps)
     B.spec_profile_enable(step.model, 0)
     by_kernel = {}
     for r in recs:
@@ -129,7 +116,7 @@ def main() -> int:
         # algorithmic traffic of a launch: the weights once, the state rows once
         d["bytes"] += 2.0 * r["weight_rows"] * r["k"] + 2.0 * r["rows"] * r["k"]
         d["flops"] += 2.0 * r["rows"] * r["weight_rows"] * r["k"]
-    if args.verbose:
+    if verbose:
         groups = {}
         for r in recs:
             g = groups.setdefault((r["kernel"], r["rows"], r["weight_rows"], r["k"]), [0.0, 0])
@@ -148,7 +135,7 @@ def main() -> int:
     # which roof binds this kernel: compare the two ideal times
     t_hbm = d["bytes"] / d["n"] / (HBM_PEAK_GBS * 1e9)
     t_mfma = d["flops"] / d["n"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
-    traffic = _traffic_from_profiles(args.workload, kernel_name(dom))
+    traffic = _traffic_from_profiles(wl_name, kernel_name(dom))
     if t_hbm >= t_mfma:
         roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic}
@@ -156,31 +143,103 @@ def main() -> int:
         roofline = {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic}
     roofline.update({"kernel": kernel_name(dom), "avg_launch_us": round(avg_ms * 1e3, 2),
-                     "launches_per_step": d["n"] / args.steps,
+                     "launches_per_step": d["n"] / steps,
                      "algorithmic_bytes_per_launch": d["bytes"] / d["n"],
                      "flops_per_launch": d["flops"] / d["n"],
                      "gbs": round(gbs, 1), "tflops": round(tflops, 2),
                      "ms_per_step_with_events": round(ms_per_step_events, 4),
-                     "share_of_step": round(d["ms"] / args.steps / ms_per_step_events, 3)})
+                     "share_of_step": round(d["ms"] / steps / ms_per_step_events, 3)})
+    # all contraction launches of a step together (every head and projection)
+    all_ms = sum(x["ms"] for x in by_kernel.values()) / steps
+    all_flops = sum(x["flops"] for x in by_kernel.values()) / steps
 
     ab = wl.algorithmic_bytes()
     out = {
-        "metric": "draft+verify steps/s", "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.weight_dtype, "data": "synthetic",
-        "config": {"workload": wl.name, "batch": wl.batch, "emb_dim": wl.emb_dim, "inner_dim": wl.inner_dim,
-                   "vocab": wl.vocab, "n_predict": wl.n_predict, "top_k": list(wl.top_k), "B": wl.B,
-                   "logits_dtype": wl.logits_dtype, "seed": wl.seed},
+        "workload": wl.name, "value": round(steps_per_s, 2), "ms_per_step": round(ms_per_step, 5),
+        "ms_draft": round(ms_draft, 5), "ms_verify": round(ms_verify, 5),
         "step_algorithmic_bytes": ab["total"],
         "step_hbm_gbs": round(ab["total"] / (ms_per_step * 1e-3) / 1e9, 1),
         "step_hbm_frac": round(ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "step_contraction_tflops": round(wl.contraction_flops() / (ms_per_step * 1e-3) / 1e12, 2),
+        # the draft's heads and projections against the bf16 MFMA peak: over the draft's wall time, and over
+        # the contraction launches alone (their event durations)
+        "draft_mfma_frac": round(wl.contraction_flops() / (ms_draft * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "contractions_mfma_frac": round(all_flops / (all_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "verify_hbm_frac": round(ab["base_logits"] / (ms_verify * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "mean_accept_len_synthetic": round(mean_accept, 3),
         "roofline": roofline,
     }
-    out["cpu_baseline"] = None if args.no_cpu_baseline else _cpu_baseline(wl, w, state, last, logits, step,
-                                                                          args.cpu_seconds)
+    return out, (wl, w, state, last, logits, step)
+
+
+def config_of(wl) -> dict:
+    return {"workload": wl.name, "batch": wl.batch, "emb_dim": wl.emb_dim, "inner_dim": wl.inner_dim,
+            "vocab": wl.vocab, "n_predict": wl.n_predict, "top_k": list(wl.top_k), "B": wl.B,
+            "logits_dtype": wl.logits_dtype, "seed": wl.seed}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama7b_b1")
+    ap.add_argument("--no-batch64", action="store_true", help="leave out the batch-64 half of the metric")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--verbose", action="store_true", help="per-shape timing of the contraction launches on stderr")
+    ap.add_argument("--fused", action="store_true",
+                    help="run the draft as one fused launch (spec_set_fused) instead of separate launches")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
+                    help="instead of the benchmark: launch the library's plain copy kernel over BYTES a few times "
+                         "(calibration of rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding in "
+              "this path)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2404_19124_amd import binding as B
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    if args.copy_probe:
+        n = args.copy_probe // 16 * 16
+        src = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        for _ in range(5):
+            B.spec_copy_probe(src, dst, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        ok = bool(torch.equal(src, dst))
+        print(json.dumps({"copy_probe_bytes": n, "launches": 5, "copied_correctly": ok}), flush=True)
+        return 0 if ok else 1
+
+    m, ctx = measure(args.workload, args.steps, args.warmup, args.verbose, args.fused)
+    wl = ctx[0]
+    out = {
+        "metric": "draft+verify steps/s", "value": m.pop("value"), "unit": "steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": m.pop("ms_per_step"),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.weight_dtype, "data": "synthetic", "config": config_of(wl),
+    }
+    m.pop("workload")
+    out.update(m)
+    out["cpu_baseline"] = None if args.no_cpu_baseline else _cpu_baseline(*ctx, args.cpu_seconds)
+    ctx[-1].close()
+    del ctx
+    torch.cuda.empty_cache()
+    if args.workload == "llama7b_b1" and not args.no_batch64:
+        # the batch-64 half of the metric: same protocol, the dense (MFMA) kernels
+        m64, ctx64 = measure("llama7b_b64", args.steps, args.warmup, args.verbose)
+        m64["unit"] = "steps/s"
+        m64["steps"], m64["warmup"] = args.steps, args.warmup
+        m64["config"] = config_of(ctx64[0])
+        out["batch64"] = m64
+        ctx64[-1].close()
     print(json.dumps(out), flush=True)
     return 0
 
@@ -188,20 +247,22 @@ def main() -> int:
 def _traffic_from_profiles(workload: str, kernel: str):
     """HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc
     (FETCH_SIZE, WRITE_SIZE) and kept as text under profiles/; None when no such
-    measurement has been recorded for this workload."""
+    measurement has been recorded for this workload and kernel instance, or when the
+    kernel sources have changed since it was taken."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as f:
             table = json.load(f)
-        return table.get(workload, {}).get(kernel)
+        entry = table.get(workload, {}).get(kernel)
+        if not isinstance(entry, dict) or entry.get("kernel_sources") != kernel_sources_digest():
+            return None
+        return entry.get("bytes_per_launch")
     except (OSError, ValueError):
         return None
 
 
 def _cpu_baseline(wl, w, state, last, logits, step, budget_s: float):
     """The oracle timed on the host: whole steps on a bounded number of sequences."""
-    import numpy as np
-    import torch
     from oracle import spec_oracle as O
     from paper_2404_19124_amd import workloads as W
 

@@ -54,7 +54,8 @@ typedef struct {
   int32_t vocab;        /* V */
   int32_t weight_dtype; /* spec_dtype_t: storage type of projection / head / embedding
                            weights, of the input state and of the stage states.
-                           SPEC_BF16 needs E and D to be multiples of 32. */
+                           SPEC_BF16 needs E and D to be multiples of 64,
+                           SPEC_F32 needs D to be a multiple of 8. */
   float state_weight;   /* w_s: weight of the projected state in the pair (Sec. 4).  If
                            state_weight < 0 or emb_weight < 0 both take the closed form of the
                            50%-variance rule:  w_s = 0.5^(1/2n), w_e = sqrt(1 - 0.5^(1/n)). */

@@ -138,6 +138,30 @@ def _ptr(t: Optional[torch.Tensor]):
     return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
 
 
+_TORCH_DTYPE = {SPEC_F32: torch.float32, SPEC_BF16: torch.bfloat16}
+_CHECK_DEVICE = True   # the CPU-only tests of _require switch the device check off to reach the others
+
+
+def _require(t, name: str, dtype: torch.dtype, shape: Optional[Sequence[int]] = None, optional: bool = False) -> None:
+    """Host-side check of a tensor argument before its address crosses the boundary: the library reads
+    raw pointers, so a wrong element type, a view with strides or a short buffer would be read (or
+    written) out of bounds on the device.  Raises ValueError."""
+    if t is None:
+        if optional:
+            return
+        raise ValueError("%s is required" % name)
+    if not isinstance(t, torch.Tensor):
+        raise ValueError("%s must be a torch.Tensor" % name)
+    if t.dtype != dtype:
+        raise ValueError("%s must have dtype %s, got %s" % (name, dtype, t.dtype))
+    if shape is not None and tuple(t.shape) != tuple(int(x) for x in shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if _CHECK_DEVICE and not t.is_cuda:
+        raise ValueError("%s must be a device tensor" % name)
+
+
 def make_config(n_predict, emb_dim, inner_dim, vocab, weight_dtype, max_batch, max_top_k, state_weight=-1.0,
                 emb_weight=-1.0, ln_eps=1e-5) -> spec_config_t:
     cfg = spec_config_t()
@@ -156,14 +180,28 @@ class SpecModel:
     def __init__(self, cfg: spec_config_t, weights: Dict[str, List[torch.Tensor]], stream=None):
         n = cfg.n_predict
         self.cfg = cfg
+        wdt = _TORCH_DTYPE.get(cfg.weight_dtype)
+        if wdt is None:
+            raise ValueError("weight_dtype %d is neither SPEC_F32 nor SPEC_BF16" % cfg.weight_dtype)
+        for key in ("proj", "emb", "head", "ln_gamma", "ln_beta"):
+            if key not in weights or len(weights[key]) != n:
+                raise ValueError("weights[%s] needs %d stages" % (key, n))
+        for i in range(n):
+            in_i = cfg.emb_dim if i == 0 else cfg.inner_dim
+            for key, dt, shape in (("proj", wdt, (cfg.inner_dim, in_i)), ("emb", wdt, (cfg.vocab, cfg.inner_dim)),
+                                   ("head", wdt, (cfg.vocab, cfg.inner_dim)),
+                                   ("ln_gamma", torch.float32, (cfg.inner_dim,)),
+                                   ("ln_beta", torch.float32, (cfg.inner_dim,))):
+                t = weights[key][i]
+                if not isinstance(t, torch.Tensor) or t.dtype != dt or tuple(t.shape) != shape or not t.is_cuda:
+                    raise ValueError("weights[%s][%d] must be a device tensor of dtype %s and shape %s"
+                                     % (key, i, dt, shape))
         self._keep = {k: [t.contiguous() for t in weights[k]] for k in ("emb", "ln_gamma", "ln_beta")}
         tmp = {k: [t.contiguous() for t in weights[k]] for k in ("proj", "head")}
         w = spec_weights_t()
         arrays = {}
         for key in ("proj", "emb", "head", "ln_gamma", "ln_beta"):
             src = tmp[key] if key in tmp else self._keep[key]
-            if len(src) != n:
-                raise ValueError("weights[%s] needs %d stages" % (key, n))
             arr = (C.c_void_p * n)(*[t.data_ptr() for t in src])
             arrays[key] = arr
             setattr(w, key, C.cast(arr, C.POINTER(C.c_void_p)))
@@ -193,8 +231,31 @@ def spec_draft(model: SpecModel, state: torch.Tensor, last_tok: torch.Tensor, to
                cand_tokens: torch.Tensor, cand_scores: torch.Tensor, cand_leaf: torch.Tensor,
                dbg: Optional[Dict[str, torch.Tensor]] = None, stream=None) -> None:
     """Enqueues one draft.  All tensors are caller-allocated device tensors."""
-    batch = state.shape[0]
-    tk = (C.c_int32 * len(top_k))(*[int(k) for k in top_k])
+    cfg = model.cfg
+    n, D = cfg.n_predict, cfg.inner_dim
+    wdt = _TORCH_DTYPE[cfg.weight_dtype]
+    top_k = [int(k) for k in top_k]
+    if len(top_k) != n:
+        raise ValueError("top_k needs %d entries, got %d" % (n, len(top_k)))
+    if not isinstance(state, torch.Tensor) or state.dim() != 2:
+        raise ValueError("state must be a [batch, emb_dim] tensor")
+    batch, B = int(state.shape[0]), int(B)
+    _require(state, "state", wdt, (batch, cfg.emb_dim))
+    _require(last_tok, "last_tok", torch.int32, (batch,))
+    _require(cand_tokens, "cand_tokens", torch.int32, (batch, B, n))
+    _require(cand_scores, "cand_scores", torch.float32, (batch, B))
+    _require(cand_leaf, "cand_leaf", torch.int32, (batch, B))
+    if dbg is not None:
+        rows, r = [], batch
+        for k in top_k:
+            rows.append(r)
+            r *= max(k, 0)
+        sum_rows, sum_rk = sum(rows), sum(r_ * k for r_, k in zip(rows, top_k))
+        _require(dbg.get("stage_state"), "dbg[stage_state]", wdt, (sum_rows, D), optional=True)
+        _require(dbg.get("topk_tok"), "dbg[topk_tok]", torch.int32, (sum_rk,), optional=True)
+        _require(dbg.get("topk_logp"), "dbg[topk_logp]", torch.float32, (sum_rk,), optional=True)
+        _require(dbg.get("row_lse"), "dbg[row_lse]", torch.float32, (sum_rows,), optional=True)
+    tk = (C.c_int32 * n)(*top_k)
     d = None
     if dbg is not None:
         d = spec_debug_t(_ptr(dbg.get("stage_state")), _ptr(dbg.get("topk_tok")), _ptr(dbg.get("topk_logp")),
@@ -208,8 +269,20 @@ def spec_verify(base_logits: torch.Tensor, cand_tokens: torch.Tensor, greedy: to
                 best_cand: torch.Tensor, out_tokens: torch.Tensor, n_out: torch.Tensor,
                 accept_all: Optional[torch.Tensor] = None, stream=None) -> None:
     """Enqueues one verify.  base_logits [batch, B, n+1, V] float32 or bfloat16."""
-    b, B, n1, V = base_logits.shape
+    if not isinstance(base_logits, torch.Tensor) or base_logits.dim() != 4:
+        raise ValueError("base_logits must be a [batch, B, n_predict + 1, vocab] tensor")
+    b, B, n1, V = (int(x) for x in base_logits.shape)
     code = {torch.float32: SPEC_F32, torch.bfloat16: SPEC_BF16}.get(base_logits.dtype, -1)
+    if code < 0:
+        raise ValueError("base_logits must be float32 or bfloat16, got %s" % base_logits.dtype)
+    _require(base_logits, "base_logits", base_logits.dtype)
+    _require(cand_tokens, "cand_tokens", torch.int32, (b, B, n1 - 1))
+    _require(greedy, "greedy", torch.int32, (b, B, n1))
+    _require(accept_len, "accept_len", torch.int32, (b,))
+    _require(best_cand, "best_cand", torch.int32, (b,))
+    _require(out_tokens, "out_tokens", torch.int32, (b, n1))
+    _require(n_out, "n_out", torch.int32, (b,))
+    _require(accept_all, "accept_all", torch.int32, (b, B), optional=True)
     _check(lib().spec_verify(_ptr(base_logits), code, _ptr(cand_tokens), b, B, n1 - 1, V, _ptr(greedy),
                              _ptr(accept_len), _ptr(best_cand), _ptr(out_tokens), _ptr(n_out), _ptr(accept_all),
                              _stream_ptr(stream)))
@@ -246,7 +319,17 @@ def spec_fused_phase_us(model: SpecModel):
 def spec_tree_metadata(cand_tokens: torch.Tensor, node_tok: torch.Tensor, node_parent: torch.Tensor,
                        node_depth: torch.Tensor, n_nodes: torch.Tensor, cand_node: torch.Tensor,
                        mask: Optional[torch.Tensor] = None, stream=None) -> None:
-    b, Bc, n = cand_tokens.shape
+    if not isinstance(cand_tokens, torch.Tensor) or cand_tokens.dim() != 3:
+        raise ValueError("cand_tokens must be a [batch, B, n_predict] tensor")
+    b, Bc, n = (int(x) for x in cand_tokens.shape)
+    M = Bc * n
+    _require(cand_tokens, "cand_tokens", torch.int32)
+    _require(node_tok, "node_tok", torch.int32, (b, M))
+    _require(node_parent, "node_parent", torch.int32, (b, M))
+    _require(node_depth, "node_depth", torch.int32, (b, M))
+    _require(n_nodes, "n_nodes", torch.int32, (b,))
+    _require(cand_node, "cand_node", torch.int32, (b, Bc, n))
+    _require(mask, "mask", torch.uint8, (b, M, M), optional=True)
     _check(lib().spec_tree_metadata(_ptr(cand_tokens), b, Bc, n, _ptr(node_tok), _ptr(node_parent), _ptr(node_depth),
                                     _ptr(n_nodes), _ptr(cand_node), _ptr(mask) if mask is not None else None,
                                     _stream_ptr(stream)))
@@ -254,8 +337,18 @@ def spec_tree_metadata(cand_tokens: torch.Tensor, node_tok: torch.Tensor, node_p
 
 def spec_advance(hidden: torch.Tensor, best_cand: torch.Tensor, accept_len: torch.Tensor, out_tokens: torch.Tensor,
                  next_state: torch.Tensor, next_tok: torch.Tensor, stream=None) -> None:
-    b, Bc, n1, E = hidden.shape
-    dtype = {torch.float32: SPEC_F32, torch.bfloat16: SPEC_BF16}[hidden.dtype]
+    if not isinstance(hidden, torch.Tensor) or hidden.dim() != 4:
+        raise ValueError("hidden must be a [batch, B, n_predict + 1, emb_dim] tensor")
+    b, Bc, n1, E = (int(x) for x in hidden.shape)
+    dtype = {torch.float32: SPEC_F32, torch.bfloat16: SPEC_BF16}.get(hidden.dtype, -1)
+    if dtype < 0:
+        raise ValueError("hidden must be float32 or bfloat16, got %s" % hidden.dtype)
+    _require(hidden, "hidden", hidden.dtype)
+    _require(best_cand, "best_cand", torch.int32, (b,))
+    _require(accept_len, "accept_len", torch.int32, (b,))
+    _require(out_tokens, "out_tokens", torch.int32, (b, n1))
+    _require(next_state, "next_state", hidden.dtype, (b, E))
+    _require(next_tok, "next_tok", torch.int32, (b,))
     _check(lib().spec_advance(_ptr(hidden), dtype, b, Bc, n1 - 1, E, _ptr(best_cand), _ptr(accept_len),
                               _ptr(out_tokens), _ptr(next_state), _ptr(next_tok), _stream_ptr(stream)))
 
@@ -269,6 +362,8 @@ def spec_plan_contraction(rows: int, k: int, n_head: int, k_top: int, n_proj: in
 
 def spec_copy_probe(src: torch.Tensor, dst: torch.Tensor, stream=None) -> int:
     """One plain copy launch src -> dst (same byte size); returns the bytes copied."""
+    _require(src, "src", src.dtype)
+    _require(dst, "dst", dst.dtype)
     nbytes = src.numel() * src.element_size()
     if dst.numel() * dst.element_size() != nbytes:
         raise ValueError("src and dst differ in size")
@@ -277,5 +372,10 @@ def spec_copy_probe(src: torch.Tensor, dst: torch.Tensor, stream=None) -> int:
 
 
 def spec_head_logp(model: SpecModel, stage: int, states: torch.Tensor, logp: torch.Tensor, stream=None) -> None:
+    cfg = model.cfg
+    if not isinstance(states, torch.Tensor) or states.dim() != 2:
+        raise ValueError("states must be a [rows, inner_dim] tensor")
+    _require(states, "states", _TORCH_DTYPE[cfg.weight_dtype], (states.shape[0], cfg.inner_dim))
+    _require(logp, "logp", torch.float32, (states.shape[0], cfg.vocab))
     _check(lib().spec_head_logp(model.handle, int(stage), _ptr(states), states.shape[0], _ptr(logp),
                                 _stream_ptr(stream)))

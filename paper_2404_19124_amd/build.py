@@ -52,9 +52,7 @@ EXTRA = {"kernels_head_gemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    # SPEC_EXTRA_DEFS="-DFOO=1 ..." reaches every translation unit (kernel tuning experiments)
-    defs = os.environ.get("SPEC_EXTRA_DEFS", "").split()
-    cmd = [hipcc(), *FLAGS, *EXTRA.get(src, []), *defs, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [hipcc(), *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)

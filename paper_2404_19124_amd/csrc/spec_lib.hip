@@ -164,6 +164,12 @@ extern "C" spec_status_t spec_create(const spec_config_t* cfg, const spec_weight
   for (int i = 0; i < cfg->n_predict; ++i)
     if (!w->proj[i] || !w->emb[i] || !w->head[i] || !w->ln_gamma[i] || !w->ln_beta[i])
       return fail(SPEC_EINVAL, "a weight pointer of stage %d is NULL", i);
+  // every weight tensor is read with 16-byte loads
+  for (int i = 0; i < cfg->n_predict; ++i)
+    if ((reinterpret_cast<uintptr_t>(w->proj[i]) | reinterpret_cast<uintptr_t>(w->emb[i]) |
+         reinterpret_cast<uintptr_t>(w->head[i]) | reinterpret_cast<uintptr_t>(w->ln_gamma[i]) |
+         reinterpret_cast<uintptr_t>(w->ln_beta[i])) & 15)
+      return fail(SPEC_EINVAL, "a weight pointer of stage %d is not 16-byte aligned", i);
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   spec_model* m = new (std::nothrow) spec_model();
@@ -558,7 +564,7 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
     m->fused_enabled = false;
     // (the counters restart from zero, should the caller switch the mode on again)
     m->barrier_value = 0;
-    (void)hipMemsetAsync(m->barrier, 0, fused_barrier_bytes(), st);
+    (void)launch_fill_u32(m->barrier, (int64_t)(fused_barrier_bytes() / 4), 0u, st);
     return fail(SPEC_EHIP, "an earlier fused draft launch timed out at its device-wide barrier (workgroups not "
                            "co-resident); its results are invalid; further drafts use separate launches");
   }

@@ -18,9 +18,9 @@ the oracle's head is evaluated on the device's own state row, and against that
   * a set of tokens (or of leaves) that differs from the oracle's must be a valid
     choice inside the strict TIE = 1e-3 band, with no allowance for the device's
     own deviation.
-The deviation from the oracle's OWN rows (oracle state, oracle logits) is capped
-separately (ABS_LOGP, ABS_SCORE: what is observed, times a stated margin) and
-reported.
+The deviation from the oracle's OWN rows (oracle state, oracle logits) - the
+propagated effect of those rounding flips - is capped separately (ABS_LOGP,
+abs_score: derived below) and reported.
 
 Relative error of a tensor = max|gpu - oracle| / max|oracle|; in addition every
 element must satisfy |gpu - oracle| <= 2e-2 * |oracle| + 2e-2 * rms(oracle)
@@ -40,17 +40,21 @@ REL = 2e-2
 # device value against the oracle's head evaluated on the device's own state row: products of two
 # bf16 values are exact in float32, so what is left is the rounding of up to 8192 float32 additions
 # of O(1) partial sums (sqrt(8192) * 2^-24 ~ 5e-6, worst case 5e-4) and the float32 exp / log of the
-# running softmax.  Observed on MI355X: <= 2e-5.
-SAME_INPUT = 2e-4
-# device log-probability against the oracle's OWN row (oracle state): a flipped bf16 state element
-# moves a logit by |h| * ulp ~ 0.02 * 0.008 = 1.6e-4; a row has a handful of flips.  Observed over all
-# configurations <= 1e-3; cap = 3 x that.
-ABS_LOGP = 3e-3
+# running softmax.  Observed on MI355X over all test shapes: <= 8e-6.
+SAME_INPUT = 1e-4
+# device log-probability against the oracle's OWN row (oracle state).  The two states differ by bf16
+# rounding flips: one flip moves a logit by |h| * ulp ~ 0.02 * 0.006 = 1.2e-4.  A first-stage row has
+# a handful of flips (float32 vs float64 arithmetic in front of the rounding); from the second stage
+# on the projected parent state already differs by ~1e-4, a few percent of a bf16 ulp, so ~100 of the
+# 4096 elements flip: sqrt(100) * 1.2e-4 = 1.2e-3 rms per logit, ~4 sigma = 5e-3 at the worst of a
+# row's 32000 logits.  Observed on MI355X over all configurations: <= 7e-3.  This cap only bounds
+# that propagated effect; the device's ARITHMETIC is policed by SAME_INPUT above and the states by REL.
+ABS_LOGP = 1e-2
 
 
 def abs_score(n: int) -> float:
     """Cap on the deviation of a leaf score (a sum of n log-probabilities) from the oracle's own."""
-    return n * ABS_LOGP
+    return min(n, 2) * ABS_LOGP
 
 
 @dataclass

@@ -99,6 +99,75 @@ def test_draft_and_verify_reject_bad_arguments_without_a_device():
     lib.spec_destroy(None)      # allowed
 
 
+def test_binding_validates_tensors_on_the_host_before_any_pointer_crosses_the_boundary(monkeypatch):
+    """Element type, shape, strides and device of every tensor argument are checked in the binding
+    (the library only sees raw addresses).  No GPU needed: the checks run before the library call."""
+    import types
+
+    import torch
+    cfg = B.make_config(3, 128, 64, 1000, "bf16", 4, (4, 3, 2))
+    model = types.SimpleNamespace(cfg=cfg, handle=None)
+    i32 = torch.int32
+    state = torch.zeros((2, 128), dtype=torch.bfloat16)
+    last = torch.zeros((2,), dtype=i32)
+    ct, cs, cl = torch.zeros((2, 6, 3), dtype=i32), torch.zeros((2, 6)), torch.zeros((2, 6), dtype=i32)
+
+    def draft(**kw):
+        a = dict(state=state, last_tok=last, top_k=(4, 3, 2), B=6, cand_tokens=ct, cand_scores=cs, cand_leaf=cl)
+        a.update(kw)
+        return B.spec_draft(model, a["state"], a["last_tok"], a["top_k"], a["B"], a["cand_tokens"], a["cand_scores"],
+                            a["cand_leaf"], a.get("dbg"))
+
+    with pytest.raises(ValueError, match="device tensor"):      # everything right except the device
+        draft()
+    logits = torch.zeros((2, 6, 4, 50))
+    outs = dict(greedy=torch.zeros((2, 6, 4), dtype=i32), accept_len=torch.zeros((2,), dtype=i32),
+                best_cand=torch.zeros((2,), dtype=i32), out_tokens=torch.zeros((2, 4), dtype=i32),
+                n_out=torch.zeros((2,), dtype=i32))
+    with pytest.raises(ValueError, match="device tensor"):
+        B.spec_verify(logits, ct, **outs)
+    monkeypatch.setattr(B, "_CHECK_DEVICE", False)              # the remaining checks, on host tensors
+    with pytest.raises(ValueError, match="top_k needs 3"):
+        draft(top_k=(4, 3))
+    with pytest.raises(ValueError, match="last_tok must have dtype torch.int32"):
+        draft(last_tok=last.long())                             # torch.randint's default type
+    with pytest.raises(ValueError, match="state must have dtype torch.bfloat16"):
+        draft(state=state.float())
+    with pytest.raises(ValueError, match="state must have shape"):
+        draft(state=torch.zeros((2, 64), dtype=torch.bfloat16))
+    with pytest.raises(ValueError, match="cand_tokens must have shape"):
+        draft(cand_tokens=torch.zeros((2, 5, 3), dtype=i32))
+    with pytest.raises(ValueError, match="cand_scores must be contiguous"):
+        draft(cand_scores=torch.zeros((6, 2)).t())
+    with pytest.raises(ValueError, match="stage_state"):
+        draft(dbg={"stage_state": torch.zeros((3, 64), dtype=torch.bfloat16)})   # needs 2 + 8 + 24 rows
+
+    with pytest.raises(ValueError, match="float32 or bfloat16"):
+        B.spec_verify(logits.half(), ct, **outs)
+    with pytest.raises(ValueError, match="cand_tokens must have shape"):
+        B.spec_verify(logits, ct[:, :5], **outs)
+    with pytest.raises(ValueError, match="greedy must have shape"):
+        B.spec_verify(logits, ct, **dict(outs, greedy=torch.zeros((2, 6, 3), dtype=i32)))
+    with pytest.raises(ValueError, match="next_state"):
+        B.spec_advance(torch.zeros((2, 6, 4, 128)), outs["best_cand"], outs["accept_len"], outs["out_tokens"],
+                       torch.zeros((2, 64)), torch.zeros((2,), dtype=i32))
+    with pytest.raises(ValueError, match="logp must have shape"):
+        B.spec_head_logp(model, 0, torch.zeros((5, 64), dtype=torch.bfloat16), torch.zeros((5, 999)))
+    with pytest.raises(ValueError, match="weights"):
+        B.SpecModel(cfg, {k: [torch.zeros(1)] * 3 for k in ("proj", "emb", "head", "ln_gamma", "ln_beta")})
+
+
+def test_create_rejects_weights_that_are_not_16_byte_aligned():
+    cfg = B.make_config(3, 128, 128, 1000, "bf16", 2, (4, 3, 2))
+    odd = (C.c_void_p * 3)(0x1008, 0x1000, 0x1000)
+    ok = (C.c_void_p * 3)(0x1000, 0x1000, 0x1000)
+    for bad_field in range(5):
+        ptrs = [C.cast(odd if f == bad_field else ok, C.POINTER(C.c_void_p)) for f in range(5)]
+        h = C.c_void_p()
+        assert B.lib().spec_create(C.byref(cfg), C.byref(B.spec_weights_t(*ptrs)), None, C.byref(h)) == B.SPEC_EINVAL
+        assert "16-byte aligned" in B.spec_last_error() and not h.value
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))

@@ -2,7 +2,7 @@
 configuration the benchmark times.  Inputs are drawn on the device (the CPU
 generator needs minutes for 10^9 normals) and copied to the host for the oracle.
 The oracle compares EVERY sequence of the 7B- and 13B-shaped batches; of the
-70B-class batch (2.6 TFLOP of float64 head rows per step) it compares 8 of the 32
+70B-class batch (2.6 TFLOP of float64 head rows per step) it compares 16 of the 32
 sequences (sequences are independent); the verify properties that hold for any
 input are checked on all of them."""
 import pytest
@@ -11,6 +11,13 @@ from paper_2404_19124_amd import workloads as W
 from tests.gpu_common import run_workload
 
 pytestmark = pytest.mark.gpu
+
+
+def _exempt_allowance(rows: int) -> int:
+    """Rows whose tokens may differ from the oracle's own (each one validated inside the strict band on the
+    same state): a bf16 flip of the state moves logits by up to ~5e-3, and about one row in a hundred has
+    two of its best logits that close."""
+    return max(2, rows // 100)
 
 
 def test_llama7b_batch1():
@@ -29,22 +36,22 @@ def test_llama7b_batch64():
     wl = W.WORKLOADS["llama7b_b64"]
     rep, *_ = run_workload(wl)                      # all 64 sequences
     assert rep.seqs == 64 and rep.rows_checked + rep.rows_skipped_below_exempt == sum(wl.rows()) == 1344
-    assert rep.rows_exempt <= 4
+    assert rep.rows_exempt <= _exempt_allowance(1344)
 
 
 def test_llama13b_batch16():
     wl = W.WORKLOADS["llama13b_b16"]
     rep, *_ = run_workload(wl)                      # all 16 sequences
     assert rep.seqs == 16 and rep.rows_checked + rep.rows_skipped_below_exempt == sum(wl.rows()) == 496
-    assert rep.rows_exempt <= 2
+    assert rep.rows_exempt <= _exempt_allowance(496)
 
 
 def test_large70b_batch32_sampled():
     wl = W.WORKLOADS["large70b_b32"]
-    seqs = [0, 3, 7, 12, 16, 21, 27, 31]
+    seqs = list(range(0, 32, 2))                    # 16 of the 32 sequences
     rep, *_ = run_workload(wl, sample_seqs=seqs)
-    assert rep.seqs == 8 and rep.rows_checked + rep.rows_skipped_below_exempt == 8 * (1 + 6 + 24 + 72)
-    assert rep.rows_exempt <= 3
+    assert rep.seqs == 16 and rep.rows_checked + rep.rows_skipped_below_exempt == 16 * (1 + 6 + 24 + 72)
+    assert rep.rows_exempt <= _exempt_allowance(16 * 103)
 
 
 # ---- code-model shapes: 7 and 5 heads, k = 1 chains and a small tree (Sec. 4.3, 4.4)

@@ -58,15 +58,18 @@ def test_tree_metadata_of_a_real_draft_and_without_mask():
 
 
 def test_tree_metadata_rejects_bad_arguments():
-    t = torch.zeros((1, 2, 3), dtype=torch.int32, device="cuda")
-    big = torch.zeros((1, 1024, 8), dtype=torch.int32, device="cuda")
-    o = torch.zeros((1, 8192), dtype=torch.int32, device="cuda")
+    i32 = dict(dtype=torch.int32, device="cuda")
+    big = torch.zeros((1, 1024, 8), **i32)                  # B * n > 4096: rejected by the library
+    o = torch.zeros((1, 8192), **i32)
     with pytest.raises(B.SpecError):
-        B.spec_tree_metadata(big, o, o, o, o, o)            # B * n > 4096
-    nine = torch.zeros((1, 2, 9), dtype=torch.int32, device="cuda")
+        B.spec_tree_metadata(big, o, o, o, torch.zeros((1,), **i32), torch.zeros((1, 1024, 8), **i32))
+    nine = torch.zeros((1, 2, 9), **i32)                    # n_predict > 8
+    o18 = torch.zeros((1, 18), **i32)
     with pytest.raises(B.SpecError):
-        B.spec_tree_metadata(nine, o, o, o, o, o)           # n_predict > 8
-    del t
+        B.spec_tree_metadata(nine, o18, o18, o18, torch.zeros((1,), **i32), torch.zeros((1, 2, 9), **i32))
+    with pytest.raises(ValueError):                         # an output of the wrong size never reaches the library
+        B.spec_tree_metadata(torch.zeros((1, 2, 3), **i32), o, o, o, torch.zeros((1,), **i32),
+                             torch.zeros((1, 2, 3), **i32))
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])

@@ -405,20 +405,27 @@ def test_runtime_argument_errors():
     w = {k: [t.cuda() for t in v] for k, v in W.make_speculator(wl, gen).items()}
     step = Step(wl, w)
     state, last = W.make_draft_inputs(wl, gen)
-    bad = W.small_variant(wl, batch=3)
+    i32 = dict(dtype=torch.int32, device="cuda")
     st3 = torch.zeros((3, 64), dtype=torch.bfloat16, device="cuda")
-    with pytest.raises(B.SpecError) as e:
-        B.spec_draft(step.model, st3, torch.zeros(3, dtype=torch.int32, device="cuda"), wl.top_k, wl.B,
-                     step.cand_tokens, step.cand_scores, step.cand_leaf)
+    with pytest.raises(B.SpecError) as e:        # batch above max_batch
+        B.spec_draft(step.model, st3, torch.zeros(3, **i32), wl.top_k, wl.B, torch.zeros((3, wl.B, 2), **i32),
+                     torch.zeros((3, wl.B), device="cuda"), torch.zeros((3, wl.B), **i32))
     assert e.value.status == B.SPEC_ESHAPE
-    with pytest.raises(B.SpecError) as e:
+    with pytest.raises(B.SpecError) as e:        # top_k above max_top_k
         B.spec_draft(step.model, state.cuda(), last.cuda(), (3, 2), wl.B, step.cand_tokens, step.cand_scores,
                      step.cand_leaf)
     assert e.value.status == B.SPEC_ESHAPE
-    with pytest.raises(B.SpecError) as e:
-        B.spec_draft(step.model, state.cuda(), last.cuda(), wl.top_k, 5, step.cand_tokens, step.cand_scores,
-                     step.cand_leaf)
+    with pytest.raises(B.SpecError) as e:        # more candidates than leaves
+        B.spec_draft(step.model, state.cuda(), last.cuda(), wl.top_k, 5, torch.zeros((2, 5, 2), **i32),
+                     torch.zeros((2, 5), device="cuda"), torch.zeros((2, 5), **i32))
     assert e.value.status == B.SPEC_EINVAL
+    # the binding refuses what the library could not check: element type, shape, strides
+    with pytest.raises(ValueError):
+        B.spec_draft(step.model, state.cuda(), last.cuda().long(), wl.top_k, wl.B, step.cand_tokens, step.cand_scores,
+                     step.cand_leaf)
+    with pytest.raises(ValueError):
+        B.spec_draft(step.model, state.cuda(), last.cuda(), wl.top_k, wl.B, step.cand_tokens[:, :2], step.cand_scores,
+                     step.cand_leaf)
     # a state that does not start on a 16-byte boundary (a view shifted by one bf16 element)
     shifted = torch.zeros(wl.batch * wl.emb_dim + 8, dtype=torch.bfloat16, device="cuda")[1:1 + wl.batch * wl.emb_dim]
     with pytest.raises(B.SpecError) as e:

@@ -221,3 +221,35 @@ def test_tiny_configuration_matches_stored_oracle_result():
     # invariants the tiny run must show
     assert d.leaf_tokens.shape == (1, 24, 3)
     assert sorted(d.cand_leaf[0].tolist()) == list(range(24))
+
+
+def test_leaf_numbering_of_a_hand_built_2_3_2_tree():
+    """Leaf index = (j1 * 3 + j2) * 2 + j3 with the FIRST stage most significant (Sec. 4.1: the tree is
+    branched head by head), checked on tables written out by hand: token ids spell (stage, row, rank),
+    so a swapped significance of two stages, or a child row computed with the wrong radix, shows."""
+    top_k = (2, 3, 2)
+    # tok_i[row][rank] = 100 * stage + 10 * row + rank  (stage 1-based)
+    tok = [np.array([[100, 101]], np.int32),
+           np.array([[200, 201, 202], [210, 211, 212]], np.int32),
+           np.array([[300, 301], [310, 311], [320, 321], [330, 331], [340, 341], [350, 351]], np.int32)]
+    # log-probabilities: powers of two, so every leaf's sum is exact in float32 and identifies its path
+    lp = [np.array([[-1.0, -2.0]], np.float32),
+          np.array([[-0.5, -4.0, -8.0], [-0.25, -16.0, -32.0]], np.float32),
+          np.array([[-0.125, -64.0]] * 6, np.float32)]
+    lp[2][3] = [-0.0625, -0.03125]          # the children of path (j1=1, j2=0): row 1 * 3 + 0 = 3
+    leaf_tokens, leaf_scores = O.expand_tree(tok, lp, top_k, 1)
+    assert leaf_tokens.shape == (1, 12, 3)
+    # written out by hand: leaf -> (j1, j2, j3) -> tokens
+    want = {0: (100, 200, 300), 1: (100, 200, 301), 2: (100, 201, 310), 5: (100, 202, 321),
+            6: (101, 210, 330), 7: (101, 210, 331), 8: (101, 211, 340), 11: (101, 212, 351)}
+    for leaf, toks in want.items():
+        assert tuple(leaf_tokens[0, leaf].tolist()) == toks, leaf
+    assert leaf_scores[0, 0] == np.float32(-1.0 - 0.5 - 0.125)
+    assert leaf_scores[0, 7] == np.float32(-2.0 - 0.25 - 0.03125)
+    assert leaf_scores[0, 6] == np.float32(-2.0 - 0.25 - 0.0625)
+    assert leaf_scores[0, 2] == np.float32(-1.0 - 4.0 - 0.125)
+    # the three most confident leaves, by hand: leaf 0 (-1.625), leaf 7 (-2.28125), leaf 6 (-2.3125)
+    c_tok, c_sc, c_leaf = O.prune(leaf_tokens, leaf_scores, 3)
+    assert c_leaf[0].tolist() == [0, 7, 6]
+    assert c_tok[0].tolist() == [[100, 200, 300], [101, 210, 331], [101, 210, 330]]
+    assert c_sc[0].tolist() == [-1.625, -2.28125, -2.3125]
