@@ -100,7 +100,11 @@ def measure(wl_name: str, steps: int, warmup: int, verbose: bool = False, fused:
     ms_per_step = dt * 1e3 / steps
     steps_per_s = steps / dt
     mean_accept = float(step.accept_len.float().mean())
+    # (each half alone; a few untimed calls first: the first loop of a new launch pattern pays one-time
+    # costs in the runtime)
+    timed(lambda: step.draft(state, last, stream), max(warmup, 5))
     ms_draft = timed(lambda: step.draft(state, last, stream), steps) * 1e3 / steps
+    timed(lambda: step.verify(logits, None, stream), max(warmup, 5))
     ms_verify = timed(lambda: step.verify(logits, None, stream), steps) * 1e3 / steps
 
     # ---- dominant kernel, timed live with events around each launch
