@@ -31,6 +31,7 @@ extern "C" {
 #define SPEC_MAX_STAGES 8      /* n_predict <= 8 (the paper uses 3, 5 and 7) */
 #define SPEC_MAX_TOPK 8        /* branches per head <= 8 (the paper uses up to 6) */
 #define SPEC_MAX_LEAVES 4096   /* prod(top_k) <= 4096 per sequence */
+#define SPEC_STATIC_SCRATCH_BYTES (8 * 1024 * 1024) /* workspace of spec_draft_static, per GPU */
 
 typedef struct spec_model spec_model_t; /* opaque: packed weights, descriptors, workspace */
 
@@ -130,6 +131,26 @@ void spec_destroy(spec_model_t* m);
 spec_status_t spec_draft(spec_model_t* m, const void* state, const int32_t* last_tok, int32_t batch,
                          const int32_t* top_k, int32_t B, int32_t* cand_tokens, float* cand_scores,
                          int32_t* cand_leaf, const spec_debug_t* dbg, void* hip_stream);
+
+/* spec_draft for callers that cannot allocate device memory and must not depend on memory
+ * somebody allocated for them at run time: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments (no debug outputs), same kernels and the same
+ * results as spec_draft, but every intermediate of the call (stage states, projected states,
+ * per-part softmax / top-k results, the per-stage tables) lives in a fixed array of
+ * SPEC_STATIC_SCRATCH_BYTES that is part of the library's device image, not in the model's
+ * workspace.  The call allocates nothing and frees nothing (no hipMalloc / hipFree, no
+ * allocating library routine); it only enqueues kernels on hip_stream.
+ *   Limit: the workspace of THIS call (it grows with batch * prod(top_k) and with the widths)
+ *   must fit the array: SPEC_ESHAPE otherwise, before anything is enqueued.  A 7B-shaped
+ *   model with one sequence and the 5/3/2 tree needs 0.7 MB.
+ *   The current device must be the model's (SPEC_EINVAL).
+ *   Every call on a GPU, from any model and any stream, shares that GPU's array (each GPU the
+ *   library runs on holds its own copy until the process ends): calls that overlap in time on
+ *   one GPU race, so keep them on one stream or order them with events.  The array keeps the
+ *   last call's contents; a call writes every piece before reading it, nothing needs clearing. */
+spec_status_t spec_draft_static(spec_model_t* m, const void* state, const int32_t* last_tok, int32_t batch,
+                                const int32_t* top_k, int32_t B, int32_t* cand_tokens, float* cand_scores,
+                                int32_t* cand_leaf, void* hip_stream);
 
 /* VERIFY (Sec. 1, 3.1, 4.1, 5), greedy.
  *   base_logits dev [batch, B, n_predict+1, V] logits_dtype   position p of candidate c is the

@@ -21,7 +21,7 @@ SPEC_OK, SPEC_EINVAL, SPEC_ESHAPE, SPEC_EDTYPE, SPEC_ENOMEM, SPEC_EHIP = 0, -1, 
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecdraft.so")
 
-EXPORTS = ["spec_create", "spec_destroy", "spec_draft", "spec_verify", "spec_head_logp", "spec_model_scalars",
+EXPORTS = ["spec_create", "spec_destroy", "spec_draft", "spec_draft_static", "spec_verify", "spec_head_logp", "spec_model_scalars",
            "spec_profile_enable", "spec_profile_read", "spec_copy_probe", "spec_set_fused", "spec_fused_timeout", "spec_fused_phase_us", "spec_tree_metadata", "spec_advance", "spec_plan_contraction", "spec_last_error", "spec_version"]
 
 
@@ -76,6 +76,9 @@ def lib() -> C.CDLL:
         l.spec_draft.restype = C.c_int
         l.spec_draft.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32,
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(spec_debug_t), C.c_void_p]
+        l.spec_draft_static.restype = C.c_int
+        l.spec_draft_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         l.spec_verify.restype = C.c_int
         l.spec_verify.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -263,6 +266,29 @@ def spec_draft(model: SpecModel, state: torch.Tensor, last_tok: torch.Tensor, to
     _check(lib().spec_draft(model.handle, _ptr(state), _ptr(last_tok), batch, tk, int(B), _ptr(cand_tokens),
                             _ptr(cand_scores), _ptr(cand_leaf), C.byref(d) if d is not None else None,
                             _stream_ptr(stream)))
+
+
+def spec_draft_static(model: SpecModel, state: torch.Tensor, last_tok: torch.Tensor, top_k: Sequence[int], B: int,
+                      cand_tokens: torch.Tensor, cand_scores: torch.Tensor, cand_leaf: torch.Tensor,
+                      stream=None) -> None:
+    """spec_draft with the call's workspace in the library's static device array (no allocation)."""
+    cfg = model.cfg
+    n = cfg.n_predict
+    wdt = _TORCH_DTYPE[cfg.weight_dtype]
+    top_k = [int(k) for k in top_k]
+    if len(top_k) != n:
+        raise ValueError("top_k needs %d entries, got %d" % (n, len(top_k)))
+    if not isinstance(state, torch.Tensor) or state.dim() != 2:
+        raise ValueError("state must be a [batch, emb_dim] tensor")
+    batch, B = int(state.shape[0]), int(B)
+    _require(state, "state", wdt, (batch, cfg.emb_dim))
+    _require(last_tok, "last_tok", torch.int32, (batch,))
+    _require(cand_tokens, "cand_tokens", torch.int32, (batch, B, n))
+    _require(cand_scores, "cand_scores", torch.float32, (batch, B))
+    _require(cand_leaf, "cand_leaf", torch.int32, (batch, B))
+    tk = (C.c_int32 * n)(*top_k)
+    _check(lib().spec_draft_static(model.handle, _ptr(state), _ptr(last_tok), batch, tk, B, _ptr(cand_tokens),
+                                   _ptr(cand_scores), _ptr(cand_leaf), _stream_ptr(stream)))
 
 
 def spec_verify(base_logits: torch.Tensor, cand_tokens: torch.Tensor, greedy: torch.Tensor, accept_len: torch.Tensor,

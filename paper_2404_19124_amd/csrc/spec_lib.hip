@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -38,10 +39,26 @@ static spec_status_t hip_fail(hipError_t e, const char* what) {
     if (e_ != hipSuccess) return hip_fail(e_, #expr);  \
   } while (0)
 
+// Device memory a draft uses beyond its inputs and outputs.  Every buffer is written before it
+// is read within one call; nothing has to start at zero.
+struct Workspace {
+  void* state_in = nullptr;   // bf16: tiled copy of the caller's state (wide dense kernel only)
+  void* states = nullptr;     // current stage's states (tiled bf16 / row-major f32)
+  float* pz[2] = {nullptr, nullptr};  // projected parent states, ping-pong
+  Partials part = {};
+  int64_t part_rows_parts = 0;  // capacity in (row, part) slots
+  int32_t* tok = nullptr;     // per-stage top-k tables, concatenated
+  float* logp = nullptr;
+  float* lse = nullptr;
+  float* logits = nullptr;    // f32 path and spec_head_logp: materialised rows
+  int64_t logits_rows = 0;
+};
+
 struct spec_model {
   spec_config_t cfg;
   float w_s, w_e, eps;
   int n_cu;
+  int device;
   bool bf16;
   size_t esz;
   // library-owned copies of the contraction weights (bf16: tiled; f32: row-major)
@@ -55,16 +72,7 @@ struct spec_model {
   int64_t max_rows;          // largest R_i
   int64_t max_parent_rows;   // largest number of distinct parent states
   int64_t sum_rows, sum_rows_k;
-  void* state_in;            // bf16: tiled copy of the caller's state (batch > 16)
-  void* states;              // current stage's states (tiled bf16 / row-major f32)
-  float* pz[2];              // projected parent states, ping-pong
-  Partials part;
-  int64_t part_rows_parts;   // capacity in (row, part) slots
-  int32_t* tok;              // per-stage top-k tables, concatenated
-  float* logp;
-  float* lse;
-  float* logits;             // f32 path and spec_head_logp: materialised rows
-  int64_t logits_rows;
+  Workspace ws;
   std::vector<void*> owned;
   // live timing of contraction launches
   struct Rec { int kernel, rows, weight_rows, k; };
@@ -109,6 +117,34 @@ static spec_status_t dev_alloc(spec_model* m, T** out, size_t bytes) {
   }
   m->owned.push_back(p);
   *out = static_cast<T*>(p);
+  return SPEC_OK;
+}
+
+// ---- spec_draft_static: the same draft with its workspace in a static device array ----------
+// Each GPU the library runs on holds its own copy of the array until the process ends.  In host code
+// the array's name is only a stand-in: its device address is looked up once per device
+// (hipGetSymbolAddress) and that pointer is what kernels, copies and fills receive.
+static __device__ __align__(256) unsigned char scratch[SPEC_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the CURRENT device's copy of `scratch` (looked up on first use on that device).
+static spec_status_t scratch_of_current_device(int* device, unsigned char** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(SPEC_EINVAL, "device %d is outside the supported range", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!ptr) return fail(SPEC_EHIP, "hipGetSymbolAddress(scratch) returned a null address");
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(ptr);
+  }
+  *device = dev;
+  *out = g_scratch_ptr[dev];
   return SPEC_OK;
 }
 
@@ -196,6 +232,17 @@ extern "C" spec_status_t spec_create(const spec_config_t* cfg, const spec_weight
     return hip_fail(e, "hipGetDeviceProperties");
   }
   m->n_cu = prop.multiProcessorCount;
+  m->device = dev;
+  {
+    // set-up for spec_draft_static: this device's address of the static scratch array
+    int sdev = -1;
+    unsigned char* sptr = nullptr;
+    spec_status_t ss = scratch_of_current_device(&sdev, &sptr);
+    if (ss != SPEC_OK) {
+      free_model(m);
+      return ss;
+    }
+  }
 
   // rows per stage at the largest call
   int64_t rows = cfg->max_batch, sum_rows = 0, sum_rows_k = 0, max_rows = 0, max_parent = cfg->max_batch;
@@ -264,24 +311,24 @@ extern "C" spec_status_t spec_create(const spec_config_t* cfg, const spec_weight
   }
 
   const int64_t rows16 = (max_rows + 15) / 16 * 16, batch16 = ((int64_t)cfg->max_batch + 15) / 16 * 16;
-  TRY_FREE(dev_alloc(m, &m->states, (size_t)rows16 * D * m->esz));
-  TRY_FREE(dev_alloc(m, &m->state_in, m->bf16 ? (size_t)batch16 * E * 2 : 16));
-  HIP_TRY_FREE(hipMemsetAsync(m->states, 0, (size_t)rows16 * D * m->esz, stream));
-  if (m->bf16) HIP_TRY_FREE(hipMemsetAsync(m->state_in, 0, (size_t)batch16 * E * 2, stream));
+  TRY_FREE(dev_alloc(m, &m->ws.states, (size_t)rows16 * D * m->esz));
+  TRY_FREE(dev_alloc(m, &m->ws.state_in, m->bf16 ? (size_t)batch16 * E * 2 : 16));
+  HIP_TRY_FREE(hipMemsetAsync(m->ws.states, 0, (size_t)rows16 * D * m->esz, stream));
+  if (m->bf16) HIP_TRY_FREE(hipMemsetAsync(m->ws.state_in, 0, (size_t)batch16 * E * 2, stream));
   // (the first projection may come as kMaxKSplit partial sums of max_batch rows each)
   const int64_t pz_rows = max_parent > (int64_t)kMaxKSplit * cfg->max_batch ? max_parent : (int64_t)kMaxKSplit * cfg->max_batch;
-  for (int q = 0; q < 2; ++q) TRY_FREE(dev_alloc(m, &m->pz[q], (size_t)pz_rows * D * 4));
-  m->part_rows_parts = partial_capacity(max_rows, V, m->n_cu);
-  TRY_FREE(dev_alloc(m, &m->part.m, (size_t)m->part_rows_parts * 4));
-  TRY_FREE(dev_alloc(m, &m->part.s, (size_t)m->part_rows_parts * 4));
-  TRY_FREE(dev_alloc(m, &m->part.val, (size_t)m->part_rows_parts * kMaxTopK * 4));
-  TRY_FREE(dev_alloc(m, &m->part.idx, (size_t)m->part_rows_parts * kMaxTopK * 4));
-  TRY_FREE(dev_alloc(m, &m->tok, (size_t)sum_rows_k * 4));
-  TRY_FREE(dev_alloc(m, &m->logp, (size_t)sum_rows_k * 4));
-  TRY_FREE(dev_alloc(m, &m->lse, (size_t)sum_rows * 4));
+  for (int q = 0; q < 2; ++q) TRY_FREE(dev_alloc(m, &m->ws.pz[q], (size_t)pz_rows * D * 4));
+  m->ws.part_rows_parts = partial_capacity(max_rows, V, m->n_cu);
+  TRY_FREE(dev_alloc(m, &m->ws.part.m, (size_t)m->ws.part_rows_parts * 4));
+  TRY_FREE(dev_alloc(m, &m->ws.part.s, (size_t)m->ws.part_rows_parts * 4));
+  TRY_FREE(dev_alloc(m, &m->ws.part.val, (size_t)m->ws.part_rows_parts * kMaxTopK * 4));
+  TRY_FREE(dev_alloc(m, &m->ws.part.idx, (size_t)m->ws.part_rows_parts * kMaxTopK * 4));
+  TRY_FREE(dev_alloc(m, &m->ws.tok, (size_t)sum_rows_k * 4));
+  TRY_FREE(dev_alloc(m, &m->ws.logp, (size_t)sum_rows_k * 4));
+  TRY_FREE(dev_alloc(m, &m->ws.lse, (size_t)sum_rows * 4));
   // materialised logits: every row for the f32 path, a small window otherwise (spec_head_logp)
-  m->logits_rows = m->bf16 ? 0 : max_rows;
-  TRY_FREE(dev_alloc(m, &m->logits, (size_t)m->logits_rows * V * 4));
+  m->ws.logits_rows = m->bf16 ? 0 : max_rows;
+  TRY_FREE(dev_alloc(m, &m->ws.logits, (size_t)m->ws.logits_rows * V * 4));
 
   if (m->bf16) {
     const size_t slots = (size_t)16 * skinny_grid(m->n_cu);
@@ -458,7 +505,7 @@ extern "C" spec_status_t spec_fused_phase_us(spec_model_t* m, float* us, int32_t
 // One contraction of R state rows against head[stage] (top-k partials, or raw
 // logits into out_head) and, if proj_stage >= 0, against proj[proj_stage]
 // (stored to out_proj).  Returns the number of parts per row it produced.
-static HeadJob make_head_job(const spec_model* m, int stage, int proj_stage, const void* b_src, bool b_rowmajor,
+static HeadJob make_head_job(const spec_model* m, const Workspace& ws, int stage, int proj_stage, const void* b_src, bool b_rowmajor,
                              int b_ld, int R, int k_top, float* out_head, float* out_proj) {
   const int D = m->cfg.inner_dim, V = m->cfg.vocab;
   HeadJob job;
@@ -469,7 +516,7 @@ static HeadJob make_head_job(const spec_model* m, int stage, int proj_stage, con
   job.b_ld = b_ld;
   job.R = R;
   job.k_top = k_top;
-  job.part = m->part;
+  job.part = ws.part;
   job.out_head = out_head;
   job.ld_head = V;
   job.out_proj = out_proj;
@@ -487,11 +534,11 @@ static HeadJob make_head_job(const spec_model* m, int stage, int proj_stage, con
   return job;
 }
 
-static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, const void* b_src, bool b_rowmajor,
+static spec_status_t run_contraction(spec_model* m, const Workspace& ws, int stage, int proj_stage, const void* b_src, bool b_rowmajor,
                                      int b_ld, int R, int k_top, float* out_head, float* out_proj, int* nparts,
                                      hipStream_t st, int* proj_parts = nullptr, const FoldJob* fold = nullptr) {
   if (proj_parts) *proj_parts = 1;
-  HeadJob job = make_head_job(m, stage, proj_stage, b_src, b_rowmajor, b_ld, R, k_top, out_head, out_proj);
+  HeadJob job = make_head_job(m, ws, stage, proj_stage, b_src, b_rowmajor, b_ld, R, k_top, out_head, out_proj);
   const int K = b_ld;
   if (fold && !skinny_fits(R, job.kt)) return fail(SPEC_ESHAPE, "internal: folded stage on a contraction of %d rows", R);
   if (fold) job.fold = *fold;
@@ -505,8 +552,8 @@ static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, c
   GemmPlan pl = plan_gemm(R, k_top, job.n_head, job.n_proj, job.kt, m->n_cu);
   // the wide kernel wants tiled states; the narrow one gathers row-major rows itself
   if (b_rowmajor && pl.ni != 1) {
-    HIP_TRY(launch_pack_bf16(b_src, m->state_in, R, K, false, st));
-    job.b_src = m->state_in;
+    HIP_TRY(launch_pack_bf16(b_src, ws.state_in, R, K, false, st));
+    job.b_src = ws.state_in;
     job.b_rowmajor = 0;
   }
   if (pl.ksplit > 1) {
@@ -516,31 +563,43 @@ static spec_status_t run_contraction(spec_model* m, int stage, int proj_stage, c
   if (proj_parts) *proj_parts = pl.ksplit;
   job.nparts = pl.nparts > 0 ? pl.nparts : 1;
   *nparts = job.nparts;
-  if (stage >= 0 && !out_head && (int64_t)R * job.nparts > m->part_rows_parts)
+  if (stage >= 0 && !out_head && (int64_t)R * job.nparts > ws.part_rows_parts)
     return fail(SPEC_ESHAPE, "internal: partial workspace too small (%d rows x %d parts)", R, job.nparts);
   const int slot = prof_slot(m, pl.ni == 1 ? (pl.mi == 2 ? 1 : 2) : 1000 + 50 * pl.mi + 2 * pl.kcap + (pl.ts != 16 ? 1 : 0), R, job.n_head + job.n_proj, K);
   HIP_TRY(launch_head_gemm(job, pl, st, EV0(slot), EV1(slot)));
   return SPEC_OK;
 }
 
-extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const int32_t* last_tok, int32_t batch,
-                                    const int32_t* top_k, int32_t B, int32_t* cand_tokens, float* cand_scores,
-                                    int32_t* cand_leaf, const spec_debug_t* dbg, void* hip_stream) {
+// Host-side checks of a draft call's arguments (no HIP call).
+static spec_status_t check_draft(const spec_model_t* m, const void* state, const int32_t* last_tok, int32_t batch,
+                                 const int32_t* top_k, int32_t B, const int32_t* cand_tokens, const float* cand_scores,
+                                 const int32_t* cand_leaf) {
   if (!m) return fail(SPEC_EINVAL, "model is NULL");
   if (!state || !last_tok || !top_k || !cand_tokens || !cand_scores || !cand_leaf)
     return fail(SPEC_EINVAL, "a required pointer is NULL");
   if (batch < 1) return fail(SPEC_EINVAL, "batch = %d must be >= 1", batch);
   if (reinterpret_cast<uintptr_t>(state) & 15) return fail(SPEC_EINVAL, "state must be 16-byte aligned");
   if (batch > m->cfg.max_batch) return fail(SPEC_ESHAPE, "batch = %d exceeds max_batch = %d", batch, m->cfg.max_batch);
-  const int n = m->cfg.n_predict, E = m->cfg.emb_dim, D = m->cfg.inner_dim, V = m->cfg.vocab;
   int64_t L = 1;
-  for (int i = 0; i < n; ++i) {
+  for (int i = 0; i < m->cfg.n_predict; ++i) {
     if (top_k[i] < 1) return fail(SPEC_EINVAL, "top_k[%d] = %d must be >= 1", i, top_k[i]);
     if (top_k[i] > m->cfg.max_top_k[i])
       return fail(SPEC_ESHAPE, "top_k[%d] = %d exceeds max_top_k[%d] = %d", i, top_k[i], i, m->cfg.max_top_k[i]);
     L *= top_k[i];
   }
   if (B < 1 || B > L) return fail(SPEC_EINVAL, "B = %d outside [1, prod(top_k) = %lld]", B, (long long)L);
+  return SPEC_OK;
+}
+
+// One draft (arguments already checked) with the workspace `ws`: the model's own, or one carved
+// from the static scratch array.
+static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, bool may_fuse, const void* state,
+                                const int32_t* last_tok, int32_t batch, const int32_t* top_k, int32_t B,
+                                int32_t* cand_tokens, float* cand_scores, int32_t* cand_leaf, const spec_debug_t* dbg,
+                                void* hip_stream) {
+  const int n = m->cfg.n_predict, E = m->cfg.emb_dim, D = m->cfg.inner_dim, V = m->cfg.vocab;
+  int64_t L = 1;
+  for (int i = 0; i < n; ++i) L *= top_k[i];
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
   // rows and table offsets per stage
@@ -577,23 +636,23 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
     sj.k_prev = i == 0 ? 1 : top_k[i - 1];
     sj.D = D;
     sj.bf16 = m->bf16 ? 1 : 0;
-    sj.part = m->part;
+    sj.part = ws.part;
     sj.nparts = nparts;
     sj.V = V;
     if (i > 0) {
-      sj.prev_tok = m->tok + off[i - 1];
-      sj.prev_logp = m->logp + off[i - 1];
-      sj.prev_lse = m->lse + row_off[i - 1];
+      sj.prev_tok = ws.tok + off[i - 1];
+      sj.prev_logp = ws.logp + off[i - 1];
+      sj.prev_lse = ws.lse + row_off[i - 1];
     }
     sj.last_tok = last_tok;
-    sj.pz = m->pz[i & 1];
+    sj.pz = ws.pz[i & 1];
     sj.emb = m->emb[i];
     sj.gamma = m->gamma[i];
     sj.beta = m->beta[i];
     sj.w_s = m->w_s;
     sj.w_e = m->w_e;
     sj.eps = m->eps;
-    sj.state_out = m->states;
+    sj.state_out = ws.states;
     sj.state_dbg = (dbg && dbg->stage_state)
                        ? static_cast<void*>(static_cast<char*>(dbg->stage_state) + (size_t)row_off[i] * D * m->esz)
                        : nullptr;
@@ -612,11 +671,11 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
       tj.row_off[i] = row_off[i];
     }
     for (int i = n; i < kMaxStages; ++i) tj.top_k[i] = 1;
-    tj.part = m->part;
+    tj.part = ws.part;
     tj.nparts = nparts;
-    tj.tok = m->tok;
-    tj.logp = m->logp;
-    tj.lse = m->lse;
+    tj.tok = ws.tok;
+    tj.logp = ws.logp;
+    tj.lse = ws.lse;
     tj.cand_tokens = cand_tokens;
     tj.cand_scores = cand_scores;
     tj.cand_leaf = cand_leaf;
@@ -625,7 +684,7 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
 
   // every stage at most 16 rows (batch 1 with the paper's trees): the whole draft in one launch
   const int grid = skinny_grid(m->n_cu);
-  bool fused = m->bf16 && m->fused_enabled && R[n - 1] <= 16 && batch <= 16 &&
+  bool fused = may_fuse && m->bf16 && m->fused_enabled && R[n - 1] <= 16 && batch <= 16 &&
                fused_fits((int)R[n - 1] > batch ? (int)R[n - 1] : batch, E / 32, D / 32, grid);
   if (fused) {
     FusedJob fj;
@@ -638,7 +697,7 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
     fj.fail_flag = m->fail_dev;
     fj.clocks = m->clocks;
     fj.timeout_ticks = m->fused_timeout_ticks;
-    fj.head[0] = make_head_job(m, -1, 0, state, true, E, batch, 0, nullptr, m->fpz[0]);
+    fj.head[0] = make_head_job(m, ws, -1, 0, state, true, E, batch, 0, nullptr, m->fpz[0]);
     fj.head[0].nparts = grid;
     int64_t sum_rows = batch;
     for (int i = 0; i < n; ++i) {
@@ -646,7 +705,7 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
       fj.stage[i].pz = m->fpz[i];
       fj.stage[i].state_out = m->fstates[i];
       if (i > 0) fj.stage[i].part = m->fpart[i - 1];
-      fj.head[i + 1] = make_head_job(m, i, i + 1 < n ? i + 1 : -1, m->fstates[i], false, D, (int)R[i], top_k[i],
+      fj.head[i + 1] = make_head_job(m, ws, i, i + 1 < n ? i + 1 : -1, m->fstates[i], false, D, (int)R[i], top_k[i],
                                      nullptr, i + 1 < n ? m->fpz[i + 1] : nullptr);
       fj.head[i + 1].part = m->fpart[i];
       fj.head[i + 1].nparts = grid;
@@ -662,10 +721,10 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
     int nparts = 1, pz0_parts = 1;
     // projection of the base model's state for stage 1
     if (m->bf16) {
-      spec_status_t s = run_contraction(m, -1, 0, state, true, E, batch, 0, nullptr, m->pz[0], &nparts, st, &pz0_parts);
+      spec_status_t s = run_contraction(m, ws, -1, 0, state, true, E, batch, 0, nullptr, ws.pz[0], &nparts, st, &pz0_parts);
       if (s != SPEC_OK) return s;
     } else {
-      HIP_TRY(launch_gemm_f32(static_cast<const float*>(state), E, static_cast<const float*>(m->proj[0]), E, m->pz[0],
+      HIP_TRY(launch_gemm_f32(static_cast<const float*>(state), E, static_cast<const float*>(m->proj[0]), E, ws.pz[0],
                               D, batch, D, E, st));
     }
 
@@ -692,16 +751,16 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
       }
       const int proj_next = i + 1 < n ? i + 1 : -1;
       if (m->bf16) {
-        spec_status_t s = run_contraction(m, i, proj_next, m->states, false, D, (int)R[i], top_k[i], nullptr,
-                                          m->pz[(i + 1) & 1], &nparts, st, nullptr, folded ? &fold : nullptr);
+        spec_status_t s = run_contraction(m, ws, i, proj_next, ws.states, false, D, (int)R[i], top_k[i], nullptr,
+                                          ws.pz[(i + 1) & 1], &nparts, st, nullptr, folded ? &fold : nullptr);
         if (s != SPEC_OK) return s;
       } else {
-        const float* sf = static_cast<const float*>(m->states);
-        HIP_TRY(launch_gemm_f32(sf, D, static_cast<const float*>(m->head[i]), D, m->logits, V, (int)R[i], V, D, st));
-        HIP_TRY(launch_row_topk_f32(m->logits, V, (int)R[i], V, top_k[i], m->part, st));
+        const float* sf = static_cast<const float*>(ws.states);
+        HIP_TRY(launch_gemm_f32(sf, D, static_cast<const float*>(m->head[i]), D, ws.logits, V, (int)R[i], V, D, st));
+        HIP_TRY(launch_row_topk_f32(ws.logits, V, (int)R[i], V, top_k[i], ws.part, st));
         nparts = 1;
         if (proj_next >= 0)
-          HIP_TRY(launch_gemm_f32(sf, D, static_cast<const float*>(m->proj[proj_next]), D, m->pz[(i + 1) & 1], D,
+          HIP_TRY(launch_gemm_f32(sf, D, static_cast<const float*>(m->proj[proj_next]), D, ws.pz[(i + 1) & 1], D,
                                   (int)R[i], D, D, st));
       }
     }
@@ -710,11 +769,84 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
 
   if (dbg) {
     const int64_t nk = off[n - 1] + R[n - 1] * top_k[n - 1], nr = row_off[n - 1] + R[n - 1];
-    if (dbg->topk_tok) HIP_TRY(hipMemcpyAsync(dbg->topk_tok, m->tok, (size_t)nk * 4, hipMemcpyDeviceToDevice, st));
-    if (dbg->topk_logp) HIP_TRY(hipMemcpyAsync(dbg->topk_logp, m->logp, (size_t)nk * 4, hipMemcpyDeviceToDevice, st));
-    if (dbg->row_lse) HIP_TRY(hipMemcpyAsync(dbg->row_lse, m->lse, (size_t)nr * 4, hipMemcpyDeviceToDevice, st));
+    if (dbg->topk_tok) HIP_TRY(hipMemcpyAsync(dbg->topk_tok, ws.tok, (size_t)nk * 4, hipMemcpyDeviceToDevice, st));
+    if (dbg->topk_logp) HIP_TRY(hipMemcpyAsync(dbg->topk_logp, ws.logp, (size_t)nk * 4, hipMemcpyDeviceToDevice, st));
+    if (dbg->row_lse) HIP_TRY(hipMemcpyAsync(dbg->row_lse, ws.lse, (size_t)nr * 4, hipMemcpyDeviceToDevice, st));
   }
   return SPEC_OK;
+}
+
+extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const int32_t* last_tok, int32_t batch,
+                                    const int32_t* top_k, int32_t B, int32_t* cand_tokens, float* cand_scores,
+                                    int32_t* cand_leaf, const spec_debug_t* dbg, void* hip_stream) {
+  spec_status_t s = check_draft(m, state, last_tok, batch, top_k, B, cand_tokens, cand_scores, cand_leaf);
+  if (s != SPEC_OK) return s;
+  return draft_impl(m, m->ws, true, state, last_tok, batch, top_k, B, cand_tokens, cand_scores, cand_leaf, dbg,
+                    hip_stream);
+}
+
+// ---- spec_draft_static: the same draft, its workspace carved from the static device array ----
+// Lays the workspace of one call (batch, top_k) out inside [base, base + SPEC_STATIC_SCRATCH_BYTES):
+// sized for THIS call (not for the model's maxima), every piece on a 256-byte boundary.
+static spec_status_t carve_static(const spec_model* m, unsigned char* base, int batch, const int32_t* top_k,
+                                  Workspace* ws) {
+  const int n = m->cfg.n_predict, E = m->cfg.emb_dim, D = m->cfg.inner_dim, V = m->cfg.vocab;
+  int64_t rows = batch, sum_rows = 0, sum_rows_k = 0, max_rows = 0, max_parent = batch;
+  for (int i = 0; i < n; ++i) {
+    if (rows > max_rows) max_rows = rows;
+    if (i + 1 < n && rows > max_parent) max_parent = rows;
+    sum_rows += rows;
+    sum_rows_k += rows * top_k[i];
+    rows *= top_k[i];
+  }
+  size_t used = 0;
+  bool fits = true;
+  auto take = [&](size_t bytes) -> unsigned char* {
+    unsigned char* p = base + used;
+    used += (bytes + 255) & ~(size_t)255;
+    if (used > (size_t)SPEC_STATIC_SCRATCH_BYTES) fits = false;
+    return p;
+  };
+  const int64_t rows16 = (max_rows + 15) / 16 * 16, batch16 = ((int64_t)batch + 15) / 16 * 16;
+  const int64_t pz_rows = max_parent > (int64_t)kMaxKSplit * batch ? max_parent : (int64_t)kMaxKSplit * batch;
+  // parts per row: one per workgroup of the streaming kernel when every stage has at most 16 rows,
+  // else what the dense plans may produce
+  const int64_t cap = max_rows <= 16 && m->bf16 ? 16 * (int64_t)skinny_grid(m->n_cu) : partial_capacity(max_rows, V, m->n_cu);
+  ws->states = take((size_t)rows16 * D * m->esz);
+  ws->state_in = take(m->bf16 ? (size_t)batch16 * E * 2 : 16);
+  for (int q = 0; q < 2; ++q) ws->pz[q] = reinterpret_cast<float*>(take((size_t)pz_rows * D * 4));
+  ws->part_rows_parts = cap;
+  ws->part.m = reinterpret_cast<float*>(take((size_t)cap * 4));
+  ws->part.s = reinterpret_cast<float*>(take((size_t)cap * 4));
+  ws->part.val = reinterpret_cast<float*>(take((size_t)cap * kMaxTopK * 4));
+  ws->part.idx = reinterpret_cast<int32_t*>(take((size_t)cap * kMaxTopK * 4));
+  ws->tok = reinterpret_cast<int32_t*>(take((size_t)sum_rows_k * 4));
+  ws->logp = reinterpret_cast<float*>(take((size_t)sum_rows_k * 4));
+  ws->lse = reinterpret_cast<float*>(take((size_t)sum_rows * 4));
+  ws->logits_rows = m->bf16 ? 0 : max_rows;
+  ws->logits = reinterpret_cast<float*>(take((size_t)ws->logits_rows * V * 4));
+  if (!fits)
+    return fail(SPEC_ESHAPE, "spec_draft_static: this call needs %zu bytes of workspace, the static array holds %d "
+                             "(use spec_draft for larger batches or trees)", used, SPEC_STATIC_SCRATCH_BYTES);
+  return SPEC_OK;
+}
+
+extern "C" spec_status_t spec_draft_static(spec_model_t* m, const void* state, const int32_t* last_tok, int32_t batch,
+                                           const int32_t* top_k, int32_t B, int32_t* cand_tokens, float* cand_scores,
+                                           int32_t* cand_leaf, void* hip_stream) {
+  spec_status_t s = check_draft(m, state, last_tok, batch, top_k, B, cand_tokens, cand_scores, cand_leaf);
+  if (s != SPEC_OK) return s;
+  Workspace ws;
+  int dev = -1;
+  unsigned char* base = nullptr;
+  s = scratch_of_current_device(&dev, &base);
+  if (s != SPEC_OK) return s;
+  if (dev != m->device)
+    return fail(SPEC_EINVAL, "the model lives on device %d, the current device is %d", m->device, dev);
+  s = carve_static(m, base, batch, top_k, &ws);
+  if (s != SPEC_OK) return s;
+  return draft_impl(m, ws, false, state, last_tok, batch, top_k, B, cand_tokens, cand_scores, cand_leaf, nullptr,
+                    hip_stream);
 }
 
 extern "C" spec_status_t spec_head_logp(spec_model_t* m, int32_t stage, const void* states, int32_t rows, float* logp,
@@ -729,12 +861,12 @@ extern "C" spec_status_t spec_head_logp(spec_model_t* m, int32_t stage, const vo
   if (m->bf16) {
     int nparts = 0;
     if (skinny_fits(rows, D / 32)) {
-      spec_status_t s = run_contraction(m, stage, -1, states, true, D, rows, 0, logp, nullptr, &nparts, st);
+      spec_status_t s = run_contraction(m, m->ws, stage, -1, states, true, D, rows, 0, logp, nullptr, &nparts, st);
       if (s != SPEC_OK) return s;
     } else {
       // tile the rows into the model's state buffer, then contract with the store epilogue
-      HIP_TRY(launch_pack_bf16(states, m->states, rows, D, false, st));
-      spec_status_t s = run_contraction(m, stage, -1, m->states, false, D, rows, 0, logp, nullptr, &nparts, st);
+      HIP_TRY(launch_pack_bf16(states, m->ws.states, rows, D, false, st));
+      spec_status_t s = run_contraction(m, m->ws, stage, -1, m->ws.states, false, D, rows, 0, logp, nullptr, &nparts, st);
       if (s != SPEC_OK) return s;
     }
   } else {
