@@ -385,3 +385,75 @@ def advance(hidden: np.ndarray, best_cand: np.ndarray, accept_len: np.ndarray, o
     a = np.asarray(accept_len).astype(np.int64)
     return hidden[idx, np.asarray(best_cand).astype(np.int64), a, :].copy(), \
         np.asarray(out_tokens)[idx, a].astype(np.int32)
+
+
+# ---------------------------------------------------------------------------
+# Per-sequence speculation settings (Sec. 4.2: speculation is switched off
+# dynamically above a batch size; Sec. 5: the number of candidates is swapped
+# dynamically to the best value for each incoming request).
+# ---------------------------------------------------------------------------
+def draft_dynamic(weights: dict, state: np.ndarray, last_tok: np.ndarray, top_k_seq, B_seq, B_pad: int,
+                  w_s: Optional[float] = None, w_e: Optional[float] = None, eps: float = 1e-5,
+                  state_dtype: str = "f32"):
+    """The draft with its own tree per sequence: top_k_seq[q][i] branches at stage i and B_seq[q]
+    candidates kept for sequence q; B_seq[q] = 0 switches speculation off for that sequence (it has
+    no candidates; the step then emits only the base model's own token).  Sequences do not interact,
+    so sequence q's candidates are those of the plain draft run on q alone with q's settings.  The
+    mix weights follow the MODEL (n stages), whatever a sequence's tree looks like.
+
+    Outputs are padded to B_pad candidates: cand_tokens [b, B_pad, n] (-1), cand_scores [b, B_pad]
+    (-inf), cand_leaf [b, B_pad] (-1), n_cand [b] = B_seq; `per_seq` holds each active sequence's
+    full DraftResult."""
+    state = np.asarray(state)
+    b = state.shape[0]
+    top_k_seq = np.asarray(top_k_seq, np.int64).reshape(b, -1)
+    n = top_k_seq.shape[1]
+    B_seq = np.asarray(B_seq, np.int64).reshape(b)
+    if w_s is None or w_e is None:
+        w_s, w_e = mix_weights(n)
+    if B_seq.max(initial=0) > B_pad:
+        raise ValueError("B_pad is smaller than the largest B_seq")
+    cand_tokens = np.full((b, B_pad, n), -1, np.int32)
+    cand_scores = np.full((b, B_pad), -np.inf, np.float32)
+    cand_leaf = np.full((b, B_pad), -1, np.int32)
+    per_seq = [None] * b
+    for q in range(b):
+        Bq = int(B_seq[q])
+        if Bq == 0:
+            continue                                   # speculation off
+        r = draft(weights, state[q:q + 1], np.asarray(last_tok)[q:q + 1], [int(k) for k in top_k_seq[q]], Bq,
+                  w_s=w_s, w_e=w_e, eps=eps, state_dtype=state_dtype, keep_logits=True)
+        cand_tokens[q, :Bq] = r.cand_tokens[0]
+        cand_scores[q, :Bq] = r.cand_scores[0]
+        cand_leaf[q, :Bq] = r.cand_leaf[0]
+        per_seq[q] = r
+    return {"cand_tokens": cand_tokens, "cand_scores": cand_scores, "cand_leaf": cand_leaf,
+            "n_cand": B_seq.astype(np.int32), "per_seq": per_seq}
+
+
+def verify_dynamic(base_logits: np.ndarray, cand_tokens: np.ndarray, n_cand: np.ndarray) -> VerifyResult:
+    """Verification when sequence q has only n_cand[q] candidates (the rest of its B slots is padding).
+    With n_cand[q] >= 1 it is verify() over q's first n_cand[q] candidates.  With n_cand[q] = 0
+    (speculation off) the base model ran an ordinary decoding step: only base_logits[q, 0, 0] exists, its
+    greedy token is the step's one output (accept_len 0, n_out 1).  Positions that were not evaluated have
+    greedy = -1 and accept_all = 0."""
+    b, B, n1, V = base_logits.shape
+    n = n1 - 1
+    greedy = np.full((b, B, n1), -1, np.int32)
+    accept_all = np.zeros((b, B), np.int32)
+    accept_len = np.zeros((b,), np.int32)
+    best_cand = np.zeros((b,), np.int32)
+    out_tokens = np.full((b, n1), -1, np.int32)
+    for q in range(b):
+        nc = int(n_cand[q])
+        if nc == 0:
+            greedy[q, 0, 0] = int(np.argmax(base_logits[q, 0, 0]))
+            out_tokens[q, 0] = greedy[q, 0, 0]
+            continue
+        r = verify(base_logits[q:q + 1, :nc], cand_tokens[q:q + 1, :nc])
+        greedy[q, :nc] = r.greedy[0]
+        accept_all[q, :nc] = r.accept_all[0]
+        accept_len[q] = r.accept_len[0]
+        best_cand[q] = r.best_cand[0]
+        out_tokens[q] = r.out_tokens[0]
+    return VerifyResult(accept_len, best_cand, out_tokens, accept_len + 1, greedy, accept_all)
