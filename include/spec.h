@@ -132,6 +132,31 @@ spec_status_t spec_draft(spec_model_t* m, const void* state, const int32_t* last
                          const int32_t* top_k, int32_t B, int32_t* cand_tokens, float* cand_scores,
                          int32_t* cand_leaf, const spec_debug_t* dbg, void* hip_stream);
 
+/* DRAFT with per-sequence speculation settings (Sec. 4.2: speculation is switched off dynamically
+ * above a batch size; Sec. 5: the number of candidates is swapped dynamically to the best value for
+ * each request).  Sequence q gets its own tree top_k_seq[q][0..n) and keeps B_seq[q] candidates;
+ * B_seq[q] = 0 switches speculation off for q (no rows are computed for it).  Sequences do not
+ * interact: q's candidates are exactly those of spec_draft on q alone with q's settings.  All
+ * sequences share each stage's weight stream (one launch per stage over the ragged row set).
+ *   state, last_tok, batch                      as for spec_draft
+ *   top_k_seq  host [batch][n_predict]          1 <= top_k_seq[q][i] <= max_top_k[i]; not read where B_seq[q] = 0
+ *   B_seq      host [batch]                     0 <= B_seq[q] <= min(B_pad, prod_i top_k_seq[q][i])
+ *   B_pad                                       candidate slots per sequence in the outputs, >= 1
+ * Outputs (dev, caller-allocated):
+ *   cand_tokens [batch, B_pad, n_predict] int32, cand_scores [batch, B_pad] float32, cand_leaf [batch, B_pad]
+ *               int32: slots [0, B_seq[q]) as spec_draft writes them (leaf indices in q's own mixed radix);
+ *               the slots behind them hold -1 / -inf / -1
+ *   n_cand     [batch] int32 = B_seq (the device copy spec_verify_dynamic reads)
+ *   dbg        as for spec_draft, with the rows of a stage = those of the active sequences in batch order and
+ *              every table of stage i as wide as the widest top_k_seq[.][i] of the call
+ * The host arrays are consumed before the call returns.  Unlike spec_draft this call copies a few KB
+ * of row maps from host memory to the device on hip_stream (it enqueues kernels and two copies; it may
+ * wait for the copy of the call four calls earlier). */
+spec_status_t spec_draft_dynamic(spec_model_t* m, const void* state, const int32_t* last_tok, int32_t batch,
+                                 const int32_t* top_k_seq, const int32_t* B_seq, int32_t B_pad, int32_t* cand_tokens,
+                                 float* cand_scores, int32_t* cand_leaf, int32_t* n_cand, const spec_debug_t* dbg,
+                                 void* hip_stream);
+
 /* spec_draft for callers that cannot allocate device memory and must not depend on memory
  * somebody allocated for them at run time: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same arguments (no debug outputs), same kernels and the same
@@ -171,6 +196,17 @@ spec_status_t spec_verify(const void* base_logits, int32_t logits_dtype, const i
                           int32_t batch, int32_t B, int32_t n_predict, int32_t vocab, int32_t* greedy,
                           int32_t* accept_len, int32_t* best_cand, int32_t* out_tokens, int32_t* n_out,
                           int32_t* accept_all, void* hip_stream);
+
+/* VERIFY with per-sequence candidate counts (the counterpart of spec_draft_dynamic; Sec. 4.2, 5).
+ *   n_cand dev [batch] int32: sequence q has candidates [0, n_cand[q]) of its B slots; the others are padding
+ *   and their base_logits rows are never read.  n_cand[q] = 0 (speculation off): the base model ran an
+ *   ordinary decoding step, only base_logits[q, 0, 0, :] is read; accept_len = 0, best_cand = 0,
+ *   out_tokens[q] = { its greedy token, -1, .. }, n_out = 1.
+ * Everything else as spec_verify; greedy is -1 at positions that were not read, accept_all is 0 for padding. */
+spec_status_t spec_verify_dynamic(const void* base_logits, int32_t logits_dtype, const int32_t* cand_tokens,
+                                  const int32_t* n_cand, int32_t batch, int32_t B, int32_t n_predict, int32_t vocab,
+                                  int32_t* greedy, int32_t* accept_len, int32_t* best_cand, int32_t* out_tokens,
+                                  int32_t* n_out, int32_t* accept_all, void* hip_stream);
 
 /* Parity aid: full log-softmax rows of stage `stage`'s head for given states,
  * computed by the same contraction kernels as spec_draft with a store epilogue.

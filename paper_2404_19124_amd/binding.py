@@ -21,7 +21,7 @@ SPEC_OK, SPEC_EINVAL, SPEC_ESHAPE, SPEC_EDTYPE, SPEC_ENOMEM, SPEC_EHIP = 0, -1, 
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecdraft.so")
 
-EXPORTS = ["spec_create", "spec_destroy", "spec_draft", "spec_draft_static", "spec_verify", "spec_head_logp", "spec_model_scalars",
+EXPORTS = ["spec_create", "spec_destroy", "spec_draft", "spec_draft_static", "spec_draft_dynamic", "spec_verify", "spec_verify_dynamic", "spec_head_logp", "spec_model_scalars",
            "spec_profile_enable", "spec_profile_read", "spec_copy_probe", "spec_set_fused", "spec_fused_timeout", "spec_fused_phase_us", "spec_tree_metadata", "spec_advance", "spec_plan_contraction", "spec_last_error", "spec_version"]
 
 
@@ -79,6 +79,14 @@ def lib() -> C.CDLL:
         l.spec_draft_static.restype = C.c_int
         l.spec_draft_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32,
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.spec_draft_dynamic.restype = C.c_int
+        l.spec_draft_dynamic.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32),
+                                         C.POINTER(C.c_int32), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.POINTER(spec_debug_t), C.c_void_p]
+        l.spec_verify_dynamic.restype = C.c_int
+        l.spec_verify_dynamic.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                          C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_void_p]
         l.spec_verify.restype = C.c_int
         l.spec_verify.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -289,6 +297,89 @@ def spec_draft_static(model: SpecModel, state: torch.Tensor, last_tok: torch.Ten
     tk = (C.c_int32 * n)(*top_k)
     _check(lib().spec_draft_static(model.handle, _ptr(state), _ptr(last_tok), batch, tk, B, _ptr(cand_tokens),
                                    _ptr(cand_scores), _ptr(cand_leaf), _stream_ptr(stream)))
+
+
+def dynamic_rows(top_k_seq: Sequence[Sequence[int]], B_seq: Sequence[int]):
+    """Row bookkeeping of a spec_draft_dynamic call (argument marshalling only): rows per stage over the
+    active sequences, the widest branching per stage, and per sequence its first row at every stage."""
+    n = len(top_k_seq[0])
+    rows, kw, first = [0] * n, [1] * n, []
+    for ks, Bq in zip(top_k_seq, B_seq):
+        first.append(list(rows))
+        if Bq == 0:
+            continue
+        cnt = 1
+        for i, k in enumerate(ks):
+            rows[i] += cnt
+            kw[i] = max(kw[i], int(k))
+            cnt *= int(k)
+    return rows, kw, first
+
+
+def spec_draft_dynamic(model: SpecModel, state: torch.Tensor, last_tok: torch.Tensor,
+                       top_k_seq: Sequence[Sequence[int]], B_seq: Sequence[int], cand_tokens: torch.Tensor,
+                       cand_scores: torch.Tensor, cand_leaf: torch.Tensor, n_cand: torch.Tensor,
+                       dbg: Optional[Dict[str, torch.Tensor]] = None, stream=None) -> None:
+    """Enqueues one draft with an own tree (top_k_seq[q]) and candidate count (B_seq[q], 0 = off) per sequence."""
+    cfg = model.cfg
+    n, D = cfg.n_predict, cfg.inner_dim
+    wdt = _TORCH_DTYPE[cfg.weight_dtype]
+    if not isinstance(state, torch.Tensor) or state.dim() != 2:
+        raise ValueError("state must be a [batch, emb_dim] tensor")
+    batch = int(state.shape[0])
+    top_k_seq = [[int(k) for k in ks] for ks in top_k_seq]
+    B_seq = [int(x) for x in B_seq]
+    if len(top_k_seq) != batch or len(B_seq) != batch or any(len(ks) != n for ks in top_k_seq):
+        raise ValueError("top_k_seq must be [batch][%d] and B_seq [batch]" % n)
+    if not isinstance(cand_tokens, torch.Tensor) or cand_tokens.dim() != 3:
+        raise ValueError("cand_tokens must be a [batch, B_pad, n_predict] tensor")
+    B_pad = int(cand_tokens.shape[1])
+    _require(state, "state", wdt, (batch, cfg.emb_dim))
+    _require(last_tok, "last_tok", torch.int32, (batch,))
+    _require(cand_tokens, "cand_tokens", torch.int32, (batch, B_pad, n))
+    _require(cand_scores, "cand_scores", torch.float32, (batch, B_pad))
+    _require(cand_leaf, "cand_leaf", torch.int32, (batch, B_pad))
+    _require(n_cand, "n_cand", torch.int32, (batch,))
+    d = None
+    if dbg is not None:
+        rows, kw, _ = dynamic_rows(top_k_seq, B_seq)
+        sum_rows, sum_rk = sum(rows), sum(r * k for r, k in zip(rows, kw))
+        _require(dbg.get("stage_state"), "dbg[stage_state]", wdt, (sum_rows, D), optional=True)
+        _require(dbg.get("topk_tok"), "dbg[topk_tok]", torch.int32, (sum_rk,), optional=True)
+        _require(dbg.get("topk_logp"), "dbg[topk_logp]", torch.float32, (sum_rk,), optional=True)
+        _require(dbg.get("row_lse"), "dbg[row_lse]", torch.float32, (sum_rows,), optional=True)
+        d = spec_debug_t(_ptr(dbg.get("stage_state")), _ptr(dbg.get("topk_tok")), _ptr(dbg.get("topk_logp")),
+                         _ptr(dbg.get("row_lse")))
+    tk = (C.c_int32 * (batch * n))(*[k for ks in top_k_seq for k in ks])
+    bs = (C.c_int32 * batch)(*B_seq)
+    _check(lib().spec_draft_dynamic(model.handle, _ptr(state), _ptr(last_tok), batch, tk, bs, B_pad, _ptr(cand_tokens),
+                                    _ptr(cand_scores), _ptr(cand_leaf), _ptr(n_cand),
+                                    C.byref(d) if d is not None else None, _stream_ptr(stream)))
+
+
+def spec_verify_dynamic(base_logits: torch.Tensor, cand_tokens: torch.Tensor, n_cand: torch.Tensor,
+                        greedy: torch.Tensor, accept_len: torch.Tensor, best_cand: torch.Tensor,
+                        out_tokens: torch.Tensor, n_out: torch.Tensor, accept_all: Optional[torch.Tensor] = None,
+                        stream=None) -> None:
+    """Enqueues one verify in which sequence q has n_cand[q] candidates (0 = speculation off)."""
+    if not isinstance(base_logits, torch.Tensor) or base_logits.dim() != 4:
+        raise ValueError("base_logits must be a [batch, B, n_predict + 1, vocab] tensor")
+    b, B, n1, V = (int(x) for x in base_logits.shape)
+    code = {torch.float32: SPEC_F32, torch.bfloat16: SPEC_BF16}.get(base_logits.dtype, -1)
+    if code < 0:
+        raise ValueError("base_logits must be float32 or bfloat16, got %s" % base_logits.dtype)
+    _require(base_logits, "base_logits", base_logits.dtype)
+    _require(cand_tokens, "cand_tokens", torch.int32, (b, B, n1 - 1))
+    _require(n_cand, "n_cand", torch.int32, (b,))
+    _require(greedy, "greedy", torch.int32, (b, B, n1))
+    _require(accept_len, "accept_len", torch.int32, (b,))
+    _require(best_cand, "best_cand", torch.int32, (b,))
+    _require(out_tokens, "out_tokens", torch.int32, (b, n1))
+    _require(n_out, "n_out", torch.int32, (b,))
+    _require(accept_all, "accept_all", torch.int32, (b, B), optional=True)
+    _check(lib().spec_verify_dynamic(_ptr(base_logits), code, _ptr(cand_tokens), _ptr(n_cand), b, B, n1 - 1, V,
+                                     _ptr(greedy), _ptr(accept_len), _ptr(best_cand), _ptr(out_tokens), _ptr(n_out),
+                                     _ptr(accept_all), _stream_ptr(stream)))
 
 
 def spec_verify(base_logits: torch.Tensor, cand_tokens: torch.Tensor, greedy: torch.Tensor, accept_len: torch.Tensor,

@@ -169,29 +169,19 @@ __device__ __attribute__((noinline)) void fused_tree_phase(unsigned lds_v, unsig
   const int tid = opaque_tid(), n = J->n, batch = J->batch, G = gridDim.x;
   float* sc = reinterpret_cast<float*>(work);
   int* s_k = reinterpret_cast<int*>(sc + kMaxLeaves);
-  int64_t* s_off = reinterpret_cast<int64_t*>(s_k + kMaxStages);
-  float* merge_lds = reinterpret_cast<float*>(s_off + kMaxStages);
-  if (tid < kMaxStages) {
-    s_k[tid] = tj->top_k[tid];
-    s_off[tid] = tj->off[tid];
+  int* s_kw = s_k + kMaxStages;
+  int64_t* s_off = reinterpret_cast<int64_t*>(s_kw + kMaxStages);
+  int64_t* s_rbase = s_off + kMaxStages;
+  float* merge_lds = reinterpret_cast<float*>(s_rbase + kMaxStages);
+  (void)tid;
+  (void)n;
+  for (int q = blockIdx.x; q < batch; q += G) {
+    TreeArgs t;
+    __syncthreads();
+    tree_args_for_sequence(*tj, q, t, s_k, s_off, s_rbase, s_kw);
+    __syncthreads();
+    tree_body<NT, 4>(t, q, s_k, s_off, s_rbase, s_kw, sc, merge_lds);
   }
-  TreeArgs t;
-  t.n = n;
-  t.B = tj->B;
-  t.L = tj->L;
-  t.nparts = tj->nparts;
-  t.k_last = tj->top_k[n - 1];
-  t.off_last = tj->off[n - 1];
-  t.row_off_last = tj->row_off[n - 1];
-  t.part = tj->part;
-  t.tok = tj->tok;
-  t.logp = tj->logp;
-  t.lse = tj->lse;
-  t.cand_tokens = tj->cand_tokens;
-  t.cand_scores = tj->cand_scores;
-  t.cand_leaf = tj->cand_leaf;
-  __syncthreads();
-  for (int q = blockIdx.x; q < batch; q += G) tree_body<NT, 4>(t, q, s_k, s_off, sc, merge_lds);
 }
 
 template <int NS, int DEPTH>

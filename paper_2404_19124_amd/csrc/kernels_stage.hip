@@ -40,27 +40,20 @@ hipError_t launch_stage(const StageJob& job, hipStream_t st) {
 template <int NT, int KWAVE>
 __global__ __launch_bounds__(NT) void tree_kernel(TreeJob j) {
   __shared__ float sc[kMaxLeaves];
-  __shared__ int s_k[kMaxStages];
-  __shared__ int64_t s_off[kMaxStages];
+  __shared__ int s_k[kMaxStages], s_kw[kMaxStages];
+  __shared__ int64_t s_off[kMaxStages], s_rbase[kMaxStages];
   __shared__ float merge_lds[32 * (NT / 256)];
   TreeArgs a;
-  a.n = j.n; a.B = j.B; a.L = j.L; a.nparts = j.nparts;
-  a.k_last = 1; a.off_last = 0; a.row_off_last = 0;
-#pragma unroll
-  for (int i = 0; i < kMaxStages; ++i) {
-    if ((int)threadIdx.x == i) { s_k[i] = j.top_k[i]; s_off[i] = j.off[i]; }
-    if (i == j.n - 1) { a.k_last = j.top_k[i]; a.off_last = j.off[i]; a.row_off_last = j.row_off[i]; }
-  }
-  a.part = j.part; a.tok = j.tok; a.logp = j.logp; a.lse = j.lse;
-  a.cand_tokens = j.cand_tokens; a.cand_scores = j.cand_scores; a.cand_leaf = j.cand_leaf;
+  tree_args_for_sequence(j, blockIdx.x, a, s_k, s_off, s_rbase, s_kw);
   __syncthreads();
-  tree_body<NT, KWAVE>(a, blockIdx.x, s_k, s_off, sc, merge_lds);
+  tree_body<NT, KWAVE>(a, blockIdx.x, s_k, s_off, s_rbase, s_kw, sc, merge_lds);
 }
 
 hipError_t launch_tree(const TreeJob& job, hipStream_t st) {
-  const int k_last = job.top_k[job.n - 1];
-  const int rows_last = job.L / k_last;
-  if (k_last <= 4 && rows_last > 8)
+  // (per-sequence trees: the widest table decides the merge variant, rows_last is then an upper bound)
+  const int kw_last = job.kstride[job.n - 1];
+  const int rows_last = job.seq_desc ? kMaxLeaves : job.L / job.top_k[job.n - 1];
+  if (kw_last <= 4 && rows_last > 8)
     hipLaunchKernelGGL((tree_kernel<1024, 4>), dim3(job.batch), dim3(1024), 0, st, job);
   else
     hipLaunchKernelGGL((tree_kernel<512, kMaxTopK>), dim3(job.batch), dim3(512), 0, st, job);

@@ -12,11 +12,22 @@
 namespace specdraft {
 
 template <bool BF16, bool VEC>
-__global__ __launch_bounds__(1024) void argmax_rows_kernel(const void* logits, int V, int32_t* greedy) {
+__global__ __launch_bounds__(1024) void argmax_rows_kernel(const void* logits, int V, int B, int n1,
+                                                           const int32_t* n_cand, int32_t* greedy) {
   __shared__ float sv[16];
   __shared__ int32_t si[16];
   const int64_t row = blockIdx.x;
   const int tid = threadIdx.x;
+  if (n_cand) {
+    // per-sequence candidate counts: rows of padding candidates are not read at all
+    const int p = (int)(row % n1);
+    const int64_t qc = row / n1;
+    const int c = (int)(qc % B), nc = n_cand[qc / B];
+    if (c >= max(nc, 1) || (nc == 0 && p > 0)) {
+      if (tid == 0) greedy[row] = -1;
+      return;
+    }
+  }
   float bv = SPEC_NEG_INF;
   int32_t bi = kIdxNone;
   if (BF16) {
@@ -93,25 +104,29 @@ __global__ __launch_bounds__(1024) void argmax_rows_kernel(const void* logits, i
   if (tid == 0) greedy[row] = (bi == kIdxNone) ? 0 : bi;
 }
 
-hipError_t launch_argmax_rows(const void* logits, int bf16, int64_t rows, int V, int32_t* greedy, hipStream_t st) {
+hipError_t launch_argmax_rows(const void* logits, int bf16, int64_t rows, int V, int B, int n1, const int32_t* n_cand,
+                              int32_t* greedy, hipStream_t st) {
   const size_t esz = bf16 ? 2 : 4;
   // 16-byte loads need every row to start on a 16-byte boundary
   const bool vec = ((size_t)V * esz) % 16 == 0 && (reinterpret_cast<uintptr_t>(logits) % 16) == 0;
   dim3 grid((unsigned)rows), block(1024);
   if (bf16) {
-    if (vec) hipLaunchKernelGGL((argmax_rows_kernel<true, true>), grid, block, 0, st, logits, V, greedy);
-    else hipLaunchKernelGGL((argmax_rows_kernel<true, false>), grid, block, 0, st, logits, V, greedy);
+    if (vec) hipLaunchKernelGGL((argmax_rows_kernel<true, true>), grid, block, 0, st, logits, V, B, n1, n_cand, greedy);
+    else hipLaunchKernelGGL((argmax_rows_kernel<true, false>), grid, block, 0, st, logits, V, B, n1, n_cand, greedy);
   } else {
-    if (vec) hipLaunchKernelGGL((argmax_rows_kernel<false, true>), grid, block, 0, st, logits, V, greedy);
-    else hipLaunchKernelGGL((argmax_rows_kernel<false, false>), grid, block, 0, st, logits, V, greedy);
+    if (vec) hipLaunchKernelGGL((argmax_rows_kernel<false, true>), grid, block, 0, st, logits, V, B, n1, n_cand, greedy);
+    else hipLaunchKernelGGL((argmax_rows_kernel<false, false>), grid, block, 0, st, logits, V, B, n1, n_cand, greedy);
   }
   return hipGetLastError();
 }
 
-__global__ __launch_bounds__(64) void accept_kernel(const int32_t* greedy, const int32_t* cand, int B, int n,
-                                                    int32_t* accept_len, int32_t* best_cand, int32_t* out_tokens,
-                                                    int32_t* n_out, int32_t* accept_all) {
+__global__ __launch_bounds__(64) void accept_kernel(const int32_t* greedy, const int32_t* cand, const int32_t* n_cand,
+                                                    int B, int n, int32_t* accept_len, int32_t* best_cand,
+                                                    int32_t* out_tokens, int32_t* n_out, int32_t* accept_all) {
   const int q = blockIdx.x, lane = threadIdx.x;
+  // candidates of this sequence (the rest of its B slots is padding); none = speculation off: the
+  // first slot stands for the empty candidate, whose accepted length is 0
+  const int nc = n_cand ? n_cand[q] : B;
   // (accepted length, candidate): longer first, then smaller candidate index
   float bv = -1.f;
   int32_t bi = kIdxNone;
@@ -119,9 +134,10 @@ __global__ __launch_bounds__(64) void accept_kernel(const int32_t* greedy, const
     const int32_t* g = greedy + ((int64_t)q * B + c) * (n + 1);
     const int32_t* t = cand + ((int64_t)q * B + c) * n;
     int a = 0;
-    while (a < n && g[a] == t[a]) ++a;
+    if (c < nc)
+      while (a < n && g[a] == t[a]) ++a;
     if (accept_all) accept_all[(int64_t)q * B + c] = a;
-    if (before((float)a, c, bv, bi)) { bv = (float)a; bi = c; }
+    if (c < max(nc, 1) && before((float)a, c, bv, bi)) { bv = (float)a; bi = c; }
   }
   wave_best(bv, bi);
   const int a = (int)bv, best = bi;
@@ -135,10 +151,10 @@ __global__ __launch_bounds__(64) void accept_kernel(const int32_t* greedy, const
   for (int p = lane; p <= n; p += 64) out_tokens[(int64_t)q * (n + 1) + p] = p < a ? t[p] : (p == a ? g[a] : -1);
 }
 
-hipError_t launch_accept(const int32_t* greedy, const int32_t* cand, int batch, int B, int n, int32_t* accept_len,
-                         int32_t* best_cand, int32_t* out_tokens, int32_t* n_out, int32_t* accept_all,
-                         hipStream_t st) {
-  hipLaunchKernelGGL(accept_kernel, dim3(batch), dim3(64), 0, st, greedy, cand, B, n, accept_len, best_cand,
+hipError_t launch_accept(const int32_t* greedy, const int32_t* cand, const int32_t* n_cand, int batch, int B, int n,
+                         int32_t* accept_len, int32_t* best_cand, int32_t* out_tokens, int32_t* n_out,
+                         int32_t* accept_all, hipStream_t st) {
+  hipLaunchKernelGGL(accept_kernel, dim3(batch), dim3(64), 0, st, greedy, cand, n_cand, B, n, accept_len, best_cand,
                      out_tokens, n_out, accept_all);
   return hipGetLastError();
 }

@@ -160,12 +160,22 @@ struct StageJob {
   float w_s, w_e, eps;
   void* state_out;         // bf16: packed tiles; f32: row-major [R][D]
   void* state_dbg;         // optional row-major [R][D] copy in the storage type
+  // Per-sequence trees (Sec. 4.2, 5: own branching per request): row r hangs under row row_parent[r] of
+  // the previous stage (stage 0: under sequence row_parent[r]) as its row_rank[r]-th child; k_prev is then
+  // the width of the previous stage's tables.  Null: the uniform tree, parent = r / k_prev, rank = r % k_prev.
+  const int32_t* row_parent;
+  const int32_t* row_rank;
 };
 hipError_t launch_stage(const StageJob& job, hipStream_t st);
 
 // ---- tree: merge of the last head + leaf scores + top-B ----------------------
 struct TreeJob {
   int batch, n, B, L;
+  int B_pad;               // candidate slots per sequence in the outputs (>= B; slots past a sequence's B are padding)
+  int kstride[kMaxStages]; // width of stage i's tables and of its head's partial lists (uniform tree: = top_k[i])
+  // Per-sequence trees: seq_desc[q * (2 n + 1) + ..] = { k_0 .. k_{n-1}, first row of q at stage 0 .. n-1, B_q };
+  // B_q = 0: the sequence has no rows and gets padding only.  Null: the uniform tree below.
+  const int32_t* seq_desc;
   int top_k[kMaxStages];
   Partials part;           // last head
   int nparts;
@@ -200,10 +210,14 @@ hipError_t launch_draft_fused(const FusedJob& job, int max_rows, hipStream_t st,
                               hipEvent_t ev_stop = nullptr);
 
 // ---- verify ----------------------------------------------------------------
-hipError_t launch_argmax_rows(const void* logits, int bf16, int64_t rows, int V, int32_t* greedy, hipStream_t st);
-hipError_t launch_accept(const int32_t* greedy, const int32_t* cand, int batch, int B, int n, int32_t* accept_len,
-                         int32_t* best_cand, int32_t* out_tokens, int32_t* n_out, int32_t* accept_all,
-                         hipStream_t st);
+// n_cand (dev [batch], may be null = every sequence has B candidates): sequence q has n_cand[q] candidates;
+// only rows (q, c < max(n_cand[q], 1), p) are scanned, and of a sequence without candidates only p = 0 (the
+// base model's own next token); rows not scanned get greedy = -1.
+hipError_t launch_argmax_rows(const void* logits, int bf16, int64_t rows, int V, int B, int n1, const int32_t* n_cand,
+                              int32_t* greedy, hipStream_t st);
+hipError_t launch_accept(const int32_t* greedy, const int32_t* cand, const int32_t* n_cand, int batch, int B, int n,
+                         int32_t* accept_len, int32_t* best_cand, int32_t* out_tokens, int32_t* n_out,
+                         int32_t* accept_all, hipStream_t st);
 
 // ---- token tree of the candidates, hand-over to the next step ----------------
 constexpr int kMaxTreeItems = 4096;  // B * n_predict per sequence (3 ints of LDS each)

@@ -73,6 +73,16 @@ struct spec_model {
   int64_t max_parent_rows;   // largest number of distinct parent states
   int64_t sum_rows, sum_rows_k;
   Workspace ws;
+  // per-sequence trees (spec_draft_dynamic): row maps and sequence descriptors are built on the host in
+  // one of kDynSlots pinned buffers and copied to dyn_dev on the caller's stream; a slot is reused only
+  // after the event recorded behind its copy has completed
+  static constexpr int kDynSlots = 4;
+  int64_t dyn_ints = 0;
+  int32_t* dyn_dev = nullptr;
+  int32_t* dyn_host[kDynSlots] = {};
+  hipEvent_t dyn_ev[kDynSlots] = {};
+  bool dyn_busy[kDynSlots] = {};
+  int dyn_next = 0;
   std::vector<void*> owned;
   // live timing of contraction launches
   struct Rec { int kernel, rows, weight_rows, k; };
@@ -104,6 +114,10 @@ static void free_model(spec_model* m) {
   for (void* p : m->owned)
     if (p) (void)hipFree(p);
   if (m->fail_host) (void)hipHostFree(m->fail_host);
+  for (int q = 0; q < spec_model::kDynSlots; ++q) {
+    if (m->dyn_host[q]) (void)hipHostFree(m->dyn_host[q]);
+    if (m->dyn_ev[q]) (void)hipEventDestroy(m->dyn_ev[q]);
+  }
   delete m;
 }
 
@@ -341,6 +355,12 @@ extern "C" spec_status_t spec_create(const spec_config_t* cfg, const spec_weight
       TRY_FREE(dev_alloc(m, &m->fpart[i].idx, slots * kMaxTopK * 4));
     }
   }
+  m->dyn_ints = 2 * sum_rows + (int64_t)cfg->max_batch * (2 * n + 2) + 64;
+  TRY_FREE(dev_alloc(m, &m->dyn_dev, (size_t)m->dyn_ints * 4));
+  for (int q = 0; q < spec_model::kDynSlots; ++q) {
+    HIP_TRY_FREE(hipHostMalloc(reinterpret_cast<void**>(&m->dyn_host[q]), (size_t)m->dyn_ints * 4, hipHostMallocDefault));
+    HIP_TRY_FREE(hipEventCreateWithFlags(&m->dyn_ev[q], hipEventDisableTiming));
+  }
   TRY_FREE(dev_alloc(m, &m->barrier, fused_barrier_bytes()));
   HIP_TRY_FREE(hipMemsetAsync(m->barrier, 0, fused_barrier_bytes(), stream));
   TRY_FREE(dev_alloc(m, &m->clocks, (2 * kMaxStages + 4) * sizeof(unsigned long long)));
@@ -570,6 +590,17 @@ static spec_status_t run_contraction(spec_model* m, const Workspace& ws, int sta
   return SPEC_OK;
 }
 
+// Per-sequence trees of one call (spec_draft_dynamic): rows and table widths per stage and the
+// device copies of the row maps / sequence descriptors the stage and tree kernels read.
+struct DynPlan {
+  int64_t R[kMaxStages];             // rows per stage over all sequences
+  int kw[kMaxStages];                // widest branching per stage = table width and top-k of the head launch
+  const int32_t* parent[kMaxStages]; // dev, [R_i]
+  const int32_t* rank[kMaxStages];   // dev, [R_i]
+  const int32_t* seq_desc;           // dev, [batch][2 n + 1]
+  int B_pad;
+};
+
 // Host-side checks of a draft call's arguments (no HIP call).
 static spec_status_t check_draft(const spec_model_t* m, const void* state, const int32_t* last_tok, int32_t batch,
                                  const int32_t* top_k, int32_t B, const int32_t* cand_tokens, const float* cand_scores,
@@ -596,10 +627,12 @@ static spec_status_t check_draft(const spec_model_t* m, const void* state, const
 static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, bool may_fuse, const void* state,
                                 const int32_t* last_tok, int32_t batch, const int32_t* top_k, int32_t B,
                                 int32_t* cand_tokens, float* cand_scores, int32_t* cand_leaf, const spec_debug_t* dbg,
-                                void* hip_stream) {
+                                void* hip_stream, const DynPlan* dyn = nullptr) {
+  // dyn != nullptr: per-sequence trees; top_k then holds the widest branching per stage (dyn->kw) and B is unused
   const int n = m->cfg.n_predict, E = m->cfg.emb_dim, D = m->cfg.inner_dim, V = m->cfg.vocab;
   int64_t L = 1;
   for (int i = 0; i < n; ++i) L *= top_k[i];
+  if (dyn) L = 1;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
   // rows and table offsets per stage
@@ -607,6 +640,7 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, bool may_f
   {
     int64_t r = batch, o = 0, ro = 0;
     for (int i = 0; i < n; ++i) {
+      if (dyn) r = dyn->R[i];
       R[i] = r;
       off[i] = o;
       row_off[i] = ro;
@@ -656,6 +690,10 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, bool may_f
     sj.state_dbg = (dbg && dbg->stage_state)
                        ? static_cast<void*>(static_cast<char*>(dbg->stage_state) + (size_t)row_off[i] * D * m->esz)
                        : nullptr;
+    if (dyn) {
+      sj.row_parent = dyn->parent[i];
+      sj.row_rank = dyn->rank[i];
+    }
     return sj;
   };
   auto tree_job = [&](int nparts) {
@@ -664,8 +702,11 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, bool may_f
     tj.batch = batch;
     tj.n = n;
     tj.B = B;
+    tj.B_pad = dyn ? dyn->B_pad : B;
+    tj.seq_desc = dyn ? dyn->seq_desc : nullptr;
     tj.L = (int)L;
     for (int i = 0; i < n; ++i) {
+      tj.kstride[i] = top_k[i];
       tj.top_k[i] = top_k[i];
       tj.off[i] = off[i];
       tj.row_off[i] = row_off[i];
@@ -684,7 +725,7 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, bool may_f
 
   // every stage at most 16 rows (batch 1 with the paper's trees): the whole draft in one launch
   const int grid = skinny_grid(m->n_cu);
-  bool fused = may_fuse && m->bf16 && m->fused_enabled && R[n - 1] <= 16 && batch <= 16 &&
+  bool fused = may_fuse && !dyn && m->bf16 && m->fused_enabled && R[n - 1] <= 16 && batch <= 16 &&
                fused_fits((int)R[n - 1] > batch ? (int)R[n - 1] : batch, E / 32, D / 32, grid);
   if (fused) {
     FusedJob fj;
@@ -719,8 +760,10 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, bool may_f
     m->clocks_n = 2 * n + 4;
   } else {
     int nparts = 1, pz0_parts = 1;
+    const bool any_rows = R[0] > 0;   // (per-sequence trees: every sequence may have speculation switched off)
     // projection of the base model's state for stage 1
-    if (m->bf16) {
+    if (!any_rows) {
+    } else if (m->bf16) {
       spec_status_t s = run_contraction(m, ws, -1, 0, state, true, E, batch, 0, nullptr, ws.pz[0], &nparts, st, &pz0_parts);
       if (s != SPEC_OK) return s;
     } else {
@@ -728,7 +771,7 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, bool may_f
                               D, batch, D, E, st));
     }
 
-    for (int i = 0; i < n; ++i) {
+    for (int i = 0; any_rows && i < n; ++i) {
       StageJob sj = stage_job(i, nparts);
       if (i == 0) {
         sj.pz_parts = pz0_parts;
@@ -738,7 +781,7 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, bool may_f
       // computed inside the head's streaming kernel instead of by a launch of their own.
       FoldJob fold;
       memset(&fold, 0, sizeof(fold));
-      const bool folded = i == 0 && m->bf16 && !dbg && skinny_fits((int)R[0], D / 32) && (int)R[0] <= skinny_fold_rows(D);
+      const bool folded = i == 0 && m->bf16 && !dbg && !dyn && skinny_fits((int)R[0], D / 32) && (int)R[0] <= skinny_fold_rows(D);
       if (folded) {
         fold.enabled = 1;
         fold.D = D; fold.V = V;
@@ -783,6 +826,100 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
   if (s != SPEC_OK) return s;
   return draft_impl(m, m->ws, true, state, last_tok, batch, top_k, B, cand_tokens, cand_scores, cand_leaf, dbg,
                     hip_stream);
+}
+
+// ---- spec_draft_dynamic: own tree and candidate count per sequence -------------------------------
+extern "C" spec_status_t spec_draft_dynamic(spec_model_t* m, const void* state, const int32_t* last_tok, int32_t batch,
+                                            const int32_t* top_k_seq, const int32_t* B_seq, int32_t B_pad,
+                                            int32_t* cand_tokens, float* cand_scores, int32_t* cand_leaf,
+                                            int32_t* n_cand, const spec_debug_t* dbg, void* hip_stream) {
+  if (!m) return fail(SPEC_EINVAL, "model is NULL");
+  if (!state || !last_tok || !top_k_seq || !B_seq || !cand_tokens || !cand_scores || !cand_leaf || !n_cand)
+    return fail(SPEC_EINVAL, "a required pointer is NULL");
+  if (batch < 1) return fail(SPEC_EINVAL, "batch = %d must be >= 1", batch);
+  if (reinterpret_cast<uintptr_t>(state) & 15) return fail(SPEC_EINVAL, "state must be 16-byte aligned");
+  if (batch > m->cfg.max_batch) return fail(SPEC_ESHAPE, "batch = %d exceeds max_batch = %d", batch, m->cfg.max_batch);
+  if (B_pad < 1) return fail(SPEC_EINVAL, "B_pad = %d must be >= 1", B_pad);
+  const int n = m->cfg.n_predict;
+  DynPlan dp;
+  memset(&dp, 0, sizeof(dp));
+  dp.B_pad = B_pad;
+  int kw[kMaxStages];
+  for (int i = 0; i < n; ++i) kw[i] = 1;
+  for (int q = 0; q < batch; ++q) {
+    const int Bq = B_seq[q];
+    if (Bq < 0 || Bq > B_pad) return fail(SPEC_EINVAL, "B_seq[%d] = %d outside [0, B_pad = %d]", q, Bq, B_pad);
+    if (Bq == 0) continue;   // speculation off: the sequence's top_k entries are not read
+    int64_t L = 1;
+    for (int i = 0; i < n; ++i) {
+      const int k = top_k_seq[(int64_t)q * n + i];
+      if (k < 1) return fail(SPEC_EINVAL, "top_k_seq[%d][%d] = %d must be >= 1", q, i, k);
+      if (k > m->cfg.max_top_k[i])
+        return fail(SPEC_ESHAPE, "top_k_seq[%d][%d] = %d exceeds max_top_k[%d] = %d", q, i, k, i, m->cfg.max_top_k[i]);
+      if (k > kw[i]) kw[i] = k;
+      dp.R[i] += L;
+      L *= k;
+    }
+    if (Bq > L) return fail(SPEC_EINVAL, "B_seq[%d] = %d exceeds the %lld leaves of its tree", q, Bq, (long long)L);
+  }
+  int64_t ints = (int64_t)batch * (2 * n + 1);
+  for (int i = 0; i < n; ++i) ints += 2 * dp.R[i];
+  if (ints > m->dyn_ints) return fail(SPEC_ESHAPE, "internal: row maps of %lld words exceed the model's %lld", (long long)ints, (long long)m->dyn_ints);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+  // a free pinned slot (the copy out of it may still be pending on the caller's stream)
+  const int slot = m->dyn_next;
+  m->dyn_next = (slot + 1) % spec_model::kDynSlots;
+  if (m->dyn_busy[slot]) HIP_TRY(hipEventSynchronize(m->dyn_ev[slot]));
+  int32_t* h = m->dyn_host[slot];
+  // layout: per stage parent[R_i], rank[R_i]; then the sequence descriptors; then B_seq (for n_cand)
+  int64_t at = 0, p_at[kMaxStages], r_at[kMaxStages];
+  for (int i = 0; i < n; ++i) {
+    p_at[i] = at;
+    at += dp.R[i];
+    r_at[i] = at;
+    at += dp.R[i];
+  }
+  const int64_t d_at = at;
+  int64_t row0[kMaxStages];
+  for (int i = 0; i < n; ++i) row0[i] = 0;
+  for (int q = 0; q < batch; ++q) {
+    int32_t* d = h + d_at + (int64_t)q * (2 * n + 1);
+    const int Bq = B_seq[q];
+    d[2 * n] = Bq;
+    int64_t cnt = 1;
+    for (int i = 0; i < n; ++i) {
+      const int k = Bq > 0 ? top_k_seq[(int64_t)q * n + i] : 1;
+      d[i] = k;
+      d[n + i] = (int32_t)row0[i];
+      if (Bq > 0) {
+        const int k_prev = i == 0 ? 1 : top_k_seq[(int64_t)q * n + i - 1];
+        for (int64_t l = 0; l < cnt; ++l) {
+          // stage 0 hangs under the sequence itself; later rows under row l / k_prev of the previous stage
+          h[p_at[i] + row0[i] + l] = i == 0 ? q : (int32_t)(row0[i - 1] - cnt / k_prev + l / k_prev);
+          h[r_at[i] + row0[i] + l] = i == 0 ? 0 : (int32_t)(l % k_prev);
+        }
+        row0[i] += cnt;
+        cnt *= k;
+      }
+    }
+  }
+  // n_cand for the verify side: the B_seq values, from the same pinned slot
+  int32_t* hb = h + ints;
+  if (ints + batch > m->dyn_ints) return fail(SPEC_ESHAPE, "internal: row maps exceed the model's buffer");
+  for (int q = 0; q < batch; ++q) hb[q] = B_seq[q];
+  HIP_TRY(hipMemcpyAsync(m->dyn_dev, h, (size_t)ints * 4, hipMemcpyHostToDevice, st));
+  HIP_TRY(hipMemcpyAsync(n_cand, hb, (size_t)batch * 4, hipMemcpyHostToDevice, st));
+  HIP_TRY(hipEventRecord(m->dyn_ev[slot], st));
+  m->dyn_busy[slot] = true;
+  for (int i = 0; i < n; ++i) {
+    dp.kw[i] = kw[i];
+    dp.parent[i] = m->dyn_dev + p_at[i];
+    dp.rank[i] = m->dyn_dev + r_at[i];
+  }
+  dp.seq_desc = m->dyn_dev + d_at;
+  return draft_impl(m, m->ws, false, state, last_tok, batch, kw, 1, cand_tokens, cand_scores, cand_leaf, dbg, hip_stream,
+                    &dp);
 }
 
 // ---- spec_draft_static: the same draft, its workspace carved from the static device array ----
@@ -877,10 +1014,10 @@ extern "C" spec_status_t spec_head_logp(spec_model_t* m, int32_t stage, const vo
   return SPEC_OK;
 }
 
-extern "C" spec_status_t spec_verify(const void* base_logits, int32_t logits_dtype, const int32_t* cand_tokens,
-                                     int32_t batch, int32_t B, int32_t n_predict, int32_t vocab, int32_t* greedy,
-                                     int32_t* accept_len, int32_t* best_cand, int32_t* out_tokens, int32_t* n_out,
-                                     int32_t* accept_all, void* hip_stream) {
+static spec_status_t verify_impl(const void* base_logits, int32_t logits_dtype, const int32_t* cand_tokens,
+                                 const int32_t* n_cand, int32_t batch, int32_t B, int32_t n_predict, int32_t vocab,
+                                 int32_t* greedy, int32_t* accept_len, int32_t* best_cand, int32_t* out_tokens,
+                                 int32_t* n_out, int32_t* accept_all, void* hip_stream) {
   if (!base_logits || !cand_tokens || !greedy || !accept_len || !best_cand || !out_tokens || !n_out)
     return fail(SPEC_EINVAL, "a required pointer is NULL");
   if (logits_dtype != SPEC_F32 && logits_dtype != SPEC_BF16)
@@ -891,10 +1028,28 @@ extern "C" spec_status_t spec_verify(const void* base_logits, int32_t logits_dty
   const int64_t rows = (int64_t)batch * B * (n_predict + 1);
   if (rows > 0x7fffffffLL) return fail(SPEC_ESHAPE, "batch * B * (n_predict + 1) is too large");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  HIP_TRY(launch_argmax_rows(base_logits, logits_dtype == SPEC_BF16, rows, vocab, greedy, st));
-  HIP_TRY(launch_accept(greedy, cand_tokens, batch, B, n_predict, accept_len, best_cand, out_tokens, n_out, accept_all,
-                        st));
+  HIP_TRY(launch_argmax_rows(base_logits, logits_dtype == SPEC_BF16, rows, vocab, B, n_predict + 1, n_cand, greedy, st));
+  HIP_TRY(launch_accept(greedy, cand_tokens, n_cand, batch, B, n_predict, accept_len, best_cand, out_tokens, n_out,
+                        accept_all, st));
   return SPEC_OK;
+}
+
+extern "C" spec_status_t spec_verify(const void* base_logits, int32_t logits_dtype, const int32_t* cand_tokens,
+                                     int32_t batch, int32_t B, int32_t n_predict, int32_t vocab, int32_t* greedy,
+                                     int32_t* accept_len, int32_t* best_cand, int32_t* out_tokens, int32_t* n_out,
+                                     int32_t* accept_all, void* hip_stream) {
+  return verify_impl(base_logits, logits_dtype, cand_tokens, nullptr, batch, B, n_predict, vocab, greedy, accept_len,
+                     best_cand, out_tokens, n_out, accept_all, hip_stream);
+}
+
+extern "C" spec_status_t spec_verify_dynamic(const void* base_logits, int32_t logits_dtype, const int32_t* cand_tokens,
+                                             const int32_t* n_cand, int32_t batch, int32_t B, int32_t n_predict,
+                                             int32_t vocab, int32_t* greedy, int32_t* accept_len, int32_t* best_cand,
+                                             int32_t* out_tokens, int32_t* n_out, int32_t* accept_all,
+                                             void* hip_stream) {
+  if (!n_cand) return fail(SPEC_EINVAL, "n_cand is NULL");
+  return verify_impl(base_logits, logits_dtype, cand_tokens, n_cand, batch, B, n_predict, vocab, greedy, accept_len,
+                     best_cand, out_tokens, n_out, accept_all, hip_stream);
 }
 
 extern "C" spec_status_t spec_tree_metadata(const int32_t* cand_tokens, int32_t batch, int32_t B, int32_t n_predict,

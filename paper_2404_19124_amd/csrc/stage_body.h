@@ -21,7 +21,11 @@ __device__ __forceinline__ void stage_row(const StageJob& j, int r, float* lds) 
   float* scratch = lds;                 // NT / 64 <= 16 words
   const int tid = opaque_tid(), lane = tid & 63;
   float* merge_lds = lds + 32 + (tid >> 8) * 32;
-  const int parent = r / j.k_prev, rank = r - parent * j.k_prev;
+  int parent = r / j.k_prev, rank = r - parent * j.k_prev;
+  if (j.row_parent) {  // per-sequence trees: the host laid the rows out
+    parent = j.row_parent[r];
+    rank = j.row_rank[r];
+  }
   const int D = j.D, nchunk = D / 8;
 
   // everything that does not depend on the token is requested first: the
@@ -56,7 +60,7 @@ __device__ __forceinline__ void stage_row(const StageJob& j, int r, float* lds) 
 
   int tok;
   if (j.stage == 0) {
-    tok = j.last_tok[r];
+    tok = j.last_tok[parent];   // (uniform tree: parent == r)
   } else {
     float v[kMaxTopK];
     int32_t ix[kMaxTopK];
@@ -177,10 +181,11 @@ __device__ __forceinline__ void stage_row(const StageJob& j, int r, float* lds) 
 // head's partial results, score every leaf by the sum of its tokens' log-probabilities
 // (added in stage order), keep the B best.
 struct TreeArgs {
-  int n, B, L, k_last, nparts;
+  int n, B, B_pad, L, k_last, kw_last, nparts;
   int64_t off_last, row_off_last;   // the last stage's offsets in tok / logp and in lse
+  int64_t rbase_last;               // first row of this sequence at the last stage
   Partials part;                    // last head
-  int32_t* tok;                     // per-stage tables [R_i][k_i], concatenated
+  int32_t* tok;                     // per-stage tables [R_i][width_i], concatenated
   float* logp;
   float* lse;
   int32_t* cand_tokens;
@@ -188,40 +193,45 @@ struct TreeArgs {
   int32_t* cand_leaf;
 };
 
-// s_k / s_off: per-stage top_k and table offsets, in LDS (indexing kernel arguments with
-// a run-time stage number would make the compiler spill the argument block to scratch).
+// One sequence q of the tree step, by a whole workgroup of NT threads.
+// B candidates are kept out of L = prod(k_i) leaves; k_last = this sequence's branching at the last
+// stage, kw_last = width of the last stage's tables and partial lists (>= k_last; equal for a uniform
+// tree).  B = 0 (speculation off): only padding is written.
+// s_k / s_off / s_rbase / s_kw: per stage, in LDS (indexing kernel arguments with a run-time stage
+// number would make the compiler spill the argument block to scratch): this sequence's branching,
+// the table's element offset, this sequence's first row, the table's width.
 // sc: kMaxLeaves floats of LDS; merge_lds: (NT / 256) * 32 words.
-// KWAVE: widest k_last merged one row per wave (register-hungry for wide lists: a wave
+// KWAVE: widest kw_last merged one row per wave (register-hungry for wide lists: a wave
 // of a 1024-thread workgroup has 128 registers); wider ones are merged one row per
 // 256-thread group.  Contains workgroup barriers.
 template <int NT, int KWAVE>
-__device__ __forceinline__ void tree_body(const TreeArgs& j, int q, const int* s_k, const int64_t* s_off, float* sc,
-                                          float* merge_lds) {
+__device__ __forceinline__ void tree_body(const TreeArgs& j, int q, const int* s_k, const int64_t* s_off,
+                                          const int64_t* s_rbase, const int* s_kw, float* sc, float* merge_lds) {
   const int tid = opaque_tid(), lane = tid & 63, wave = tid >> 6;
-  const int n = j.n, L = j.L, k_last = j.k_last;
-  const int rows_last = L / k_last;
+  const int n = j.n, L = j.L, kw = j.kw_last;
+  const int rows_last = j.B > 0 ? L / j.k_last : 0;
 
-  if (k_last <= KWAVE) {
+  if (kw <= KWAVE) {
     for (int rl = wave; rl < rows_last; rl += NT / 64) {
-      const int64_t row = (int64_t)q * rows_last + rl;
+      const int64_t row = j.rbase_last + rl;
       float v[kMaxTopK];
       int32_t ix[kMaxTopK];
       float lse;
       if (KWAVE >= kMaxTopK) {
-        wave_merge_partials(j.part, row, j.nparts, k_last, v, ix, lse);
+        wave_merge_partials(j.part, row, j.nparts, kw, v, ix, lse);
       } else {
-        switch (k_last) {
-          case 1: wave_merge_partials_k<1>(j.part, row, j.nparts, k_last, v, ix, lse); break;
-          case 2: wave_merge_partials_k<2>(j.part, row, j.nparts, k_last, v, ix, lse); break;
-          case 3: wave_merge_partials_k<3>(j.part, row, j.nparts, k_last, v, ix, lse); break;
-          default: wave_merge_partials_k<4>(j.part, row, j.nparts, k_last, v, ix, lse); break;
+        switch (kw) {
+          case 1: wave_merge_partials_k<1>(j.part, row, j.nparts, kw, v, ix, lse); break;
+          case 2: wave_merge_partials_k<2>(j.part, row, j.nparts, kw, v, ix, lse); break;
+          case 3: wave_merge_partials_k<3>(j.part, row, j.nparts, kw, v, ix, lse); break;
+          default: wave_merge_partials_k<4>(j.part, row, j.nparts, kw, v, ix, lse); break;
         }
       }
 #pragma unroll
       for (int t = 0; t < kMaxTopK; ++t)
-        if (lane == t && t < k_last) {
-          j.tok[j.off_last + row * k_last + t] = ix[t];
-          j.logp[j.off_last + row * k_last + t] = v[t] - lse;
+        if (lane == t && t < kw) {
+          j.tok[j.off_last + row * kw + t] = ix[t];
+          j.logp[j.off_last + row * kw + t] = v[t] - lse;
         }
       if (lane == 0) j.lse[j.row_off_last + row] = lse;
     }
@@ -230,16 +240,16 @@ __device__ __forceinline__ void tree_body(const TreeArgs& j, int q, const int* s
     for (int r0 = 0; r0 < rows_last; r0 += NT / 256) {
       const int rl = r0 + grp;
       const bool live = rl < rows_last;
-      const int64_t row = (int64_t)q * rows_last + (live ? rl : rows_last - 1);
+      const int64_t row = j.rbase_last + (live ? rl : rows_last - 1);
       float v[kMaxTopK];
       int32_t ix[kMaxTopK];
       float lse;
-      group_merge_partials(j.part, row, j.nparts, k_last, v, ix, lse, merge_lds + grp * 32);
+      group_merge_partials(j.part, row, j.nparts, kw, v, ix, lse, merge_lds + grp * 32);
 #pragma unroll
       for (int t = 0; t < kMaxTopK; ++t)
-        if (live && gl == t && t < k_last) {
-          j.tok[j.off_last + row * k_last + t] = ix[t];
-          j.logp[j.off_last + row * k_last + t] = v[t] - lse;
+        if (live && gl == t && t < kw) {
+          j.tok[j.off_last + row * kw + t] = ix[t];
+          j.logp[j.off_last + row * kw + t] = v[t] - lse;
         }
       if (live && gl == 0) j.lse[j.row_off_last + row] = lse;
     }
@@ -247,22 +257,23 @@ __device__ __forceinline__ void tree_body(const TreeArgs& j, int q, const int* s
   __threadfence_block();
   __syncthreads();
 
-  for (int leaf = tid; leaf < L; leaf += NT) {
+  const int nleaf = j.B > 0 ? L : 0;
+  for (int leaf = tid; leaf < nleaf; leaf += NT) {
     float score = 0.f;
-    int64_t row = q;
+    int64_t local = 0;
     int stride = L;
     for (int i = 0; i < n; ++i) {
       const int k = s_k[i];
       stride /= k;
       const int rank = (leaf / stride) % k;
-      score += j.logp[s_off[i] + row * k + rank];
-      row = row * k + rank;
+      score += j.logp[s_off[i] + (s_rbase[i] + local) * s_kw[i] + rank];
+      local = local * k + rank;
     }
     sc[leaf] = score;
   }
   __syncthreads();
 
-  for (int leaf = tid; leaf < L; leaf += NT) {
+  for (int leaf = tid; leaf < nleaf; leaf += NT) {
     const float s = sc[leaf];
     int pos = 0;
     for (int o = 0; o < L; ++o) {
@@ -270,18 +281,57 @@ __device__ __forceinline__ void tree_body(const TreeArgs& j, int q, const int* s
       pos += ((so > s) || (so == s && o < leaf)) ? 1 : 0;
     }
     if (pos < j.B) {
-      const int64_t c = (int64_t)q * j.B + pos;
+      const int64_t c = (int64_t)q * j.B_pad + pos;
       j.cand_leaf[c] = leaf;
       j.cand_scores[c] = s;
-      int64_t row = q;
+      int64_t local = 0;
       int stride = L;
       for (int i = 0; i < n; ++i) {
         const int k = s_k[i];
         stride /= k;
         const int rank = (leaf / stride) % k;
-        j.cand_tokens[c * n + i] = j.tok[s_off[i] + row * k + rank];
-        row = row * k + rank;
+        j.cand_tokens[c * n + i] = j.tok[s_off[i] + (s_rbase[i] + local) * s_kw[i] + rank];
+        local = local * k + rank;
       }
+    }
+  }
+  // slots past this sequence's candidates: padding
+  for (int pos = j.B + tid; pos < j.B_pad; pos += NT) {
+    const int64_t c = (int64_t)q * j.B_pad + pos;
+    j.cand_leaf[c] = -1;
+    j.cand_scores[c] = SPEC_NEG_INF;
+    for (int i = 0; i < n; ++i) j.cand_tokens[c * n + i] = -1;
+  }
+}
+
+// Fills the per-sequence arguments of tree_body for sequence q from a TreeJob: thread 0 .. n-1 write
+// the LDS arrays, every thread computes the scalars.  Call with all threads, then __syncthreads().
+__device__ __forceinline__ void tree_args_for_sequence(const TreeJob& j, int q, TreeArgs& a, int* s_k, int64_t* s_off,
+                                                       int64_t* s_rbase, int* s_kw) {
+  const int tid = opaque_tid();
+  const int n = j.n;
+  a.n = n; a.B_pad = j.B_pad; a.nparts = j.nparts;
+  a.part = j.part; a.tok = j.tok; a.logp = j.logp; a.lse = j.lse;
+  a.cand_tokens = j.cand_tokens; a.cand_scores = j.cand_scores; a.cand_leaf = j.cand_leaf;
+  a.B = j.B; a.L = j.L; a.k_last = 1; a.kw_last = 1; a.off_last = 0; a.row_off_last = 0; a.rbase_last = 0;
+  const int32_t* d = j.seq_desc ? j.seq_desc + (int64_t)q * (2 * n + 1) : nullptr;
+  if (d) {
+    a.B = d[2 * n];
+    a.L = 1;
+  }
+  int64_t cnt = 1;   // rows of one sequence at stage i (uniform tree)
+#pragma unroll
+  for (int i = 0; i < kMaxStages; ++i) {
+    if (i < n) {
+      const int k = d ? d[i] : j.top_k[i];
+      const int64_t rbase = d ? (int64_t)d[n + i] : (int64_t)q * cnt;
+      if (d) a.L *= k;
+      if (tid == i) { s_k[i] = k; s_off[i] = j.off[i]; s_rbase[i] = rbase; s_kw[i] = j.kstride[i]; }
+      if (i == n - 1) {
+        a.k_last = k; a.kw_last = j.kstride[i]; a.off_last = j.off[i]; a.row_off_last = j.row_off[i];
+        a.rbase_last = rbase;
+      }
+      cnt *= k;
     }
   }
 }
