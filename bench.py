@@ -43,8 +43,7 @@ def kernel_name(kid: int) -> str:
     if kid >= 1000:
         mb, rest = divmod(kid - 1000, 100)
         return "head_gemm32_kernel<%d, 2, %d, %s>" % (mb, rest // 2, "true" if rest % 2 else "false")
-    return {0: "head_skinny_kernel", 1: "head_gemm_kernel<2, 1, 8>", 2: "head_gemm_kernel<4, 1, 8>",
-            4: "draft_fused_kernel"}[kid]
+    return {0: "head_skinny_kernel", 1: "head_gemm_kernel<2, 1, 8>", 2: "head_gemm_kernel<4, 1, 8>"}[kid]
 
 
 def kernel_sources_digest() -> str:
@@ -58,7 +57,7 @@ def kernel_sources_digest() -> str:
     return h.hexdigest()[:16]
 
 
-def measure(wl_name: str, steps: int, warmup: int, verbose: bool = False, fused: bool = False):
+def measure(wl_name: str, steps: int, warmup: int, verbose: bool = False):
     """Times `steps` whole steps of one workload, then the same number again with the library's
     per-launch events on, and the draft and the verify alone.  Returns (metrics dict, context for
     the CPU baseline)."""
@@ -72,8 +71,6 @@ def measure(wl_name: str, steps: int, warmup: int, verbose: bool = False, fused:
     w = W.make_speculator(wl, gen, device="cuda")
     state, last = W.make_draft_inputs(wl, gen, device="cuda")
     step = Step(wl, w)
-    if fused:
-        B.spec_set_fused(step.model, True)
     stream = torch.cuda.current_stream()
 
     # inputs of verify: logits boosted at the candidates this draft produces
@@ -192,8 +189,6 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--verbose", action="store_true", help="per-shape timing of the contraction launches on stderr")
-    ap.add_argument("--fused", action="store_true",
-                    help="run the draft as one fused launch (spec_set_fused) instead of separate launches")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
                     help="instead of the benchmark: launch the library's plain copy kernel over BYTES a few times "
                          "(calibration of rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -222,7 +217,7 @@ def main() -> int:
         print(json.dumps({"copy_probe_bytes": n, "launches": 5, "copied_correctly": ok}), flush=True)
         return 0 if ok else 1
 
-    m, ctx = measure(args.workload, args.steps, args.warmup, args.verbose, args.fused)
+    m, ctx = measure(args.workload, args.steps, args.warmup, args.verbose)
     wl = ctx[0]
     out = {
         "metric": "draft+verify steps/s", "value": m.pop("value"), "unit": "steps/s", "n_gpus": 1,

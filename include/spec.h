@@ -172,7 +172,8 @@ spec_status_t spec_draft_dynamic(spec_model_t* m, const void* state, const int32
  *   Every call on a GPU, from any model and any stream, shares that GPU's array (each GPU the
  *   library runs on holds its own copy until the process ends): calls that overlap in time on
  *   one GPU race, so keep them on one stream or order them with events.  The array keeps the
- *   last call's contents; a call writes every piece before reading it, nothing needs clearing. */
+ *   last call's contents: a call writes every piece before reading it, except a few counters that
+ *   are zero when the library is loaded and that every launch using them sets back to zero. */
 spec_status_t spec_draft_static(spec_model_t* m, const void* state, const int32_t* last_tok, int32_t batch,
                                 const int32_t* top_k, int32_t B, int32_t* cand_tokens, float* cand_scores,
                                 int32_t* cand_leaf, void* hip_stream);
@@ -220,7 +221,6 @@ spec_status_t spec_head_logp(spec_model_t* m, int32_t stage, const void* states,
  * caller's stream); nothing else changes.
  *   kernel: 0 = rows<=16 streaming kernel (head_skinny_kernel),
  *           1, 2 = narrow dense kernel head_gemm_kernel<MI,1,8> with MI = 2, 4 (32- / 64-row state blocks),
- *           4 = whole draft in one launch (rows / weight_rows summed over its contractions),
  *           1000 + 100 * MB + 2 * KT + VT = wide dense kernel head_gemm32_kernel<MB,2,KT,VT>
  *           (32 * MB-row state blocks, per-lane top-k lists of KT entries, VT = 1 with short tiles)
  *   rows, weight_rows, k: the contraction is [rows, k] x [weight_rows, k]^T
@@ -268,30 +268,6 @@ spec_status_t spec_tree_metadata(const int32_t* cand_tokens, int32_t batch, int3
 spec_status_t spec_advance(const void* hidden, int32_t hidden_dtype, int32_t batch, int32_t B, int32_t n_predict,
                            int32_t emb_dim, const int32_t* best_cand, const int32_t* accept_len,
                            const int32_t* out_tokens, void* next_state, int32_t* next_tok, void* hip_stream);
-
-/* Optional launch mode of spec_draft, OFF by default.  When enabled and every stage of a
- * call has at most 16 rows (batch 1 with the paper's trees) and the model is SPEC_BF16 with
- * emb_dim == inner_dim in {512, 1024, 2048, 3072, 4096}, spec_draft runs the whole draft
- * (Sec. 3.1, 4.1) as ONE kernel launch whose phases are separated by a device-wide
- * barrier instead of a sequence of launches.  Both modes give bit-identical results; on
- * MI355X the sequence of launches is the faster one (a kernel boundary costs less than
- * the barrier), which is why it is the default.  The fused launch needs all its
- * workgroups resident at once (one per compute unit); should that not hold, its barrier
- * gives up after about 2 s, the NEXT spec_draft on the model returns SPEC_EHIP (the
- * candidates of the failed call are invalid) and the mode switches itself off. */
-spec_status_t spec_set_fused(spec_model_t* m, int32_t enable);
-
-/* Bound of one wait at the fused launch's device-wide barrier (default 2 s).  With 0 a workgroup
- * that finds a barrier not yet complete gives up at once: every workgroup then leaves the kernel
- * normally, which exercises the failure handling described above without hanging anything. */
-spec_status_t spec_fused_timeout(spec_model_t* m, int64_t microseconds);
-
-/* Durations, in microseconds, between the phase boundaries of the model's last fused
- * draft launch as seen by its first workgroup: [proj_1][barrier][stage_1 + barrier + head_1]
- * [barrier][stage_2 + barrier + head_2] ... [barrier][tree].  Synchronises with the device
- * (call after the stream is idle).  us: host array of `cap` floats; *n (host) receives the
- * number written (0 when no fused launch has run). */
-spec_status_t spec_fused_phase_us(spec_model_t* m, float* us, int32_t cap, int32_t* n);
 
 /* Measurement aid, not a step of the method: one launch of a plain copy kernel that
  * reads `bytes` from src (dev) and writes them to dst (dev; must not overlap src).  Its HBM

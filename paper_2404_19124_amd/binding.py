@@ -22,7 +22,7 @@ SPEC_OK, SPEC_EINVAL, SPEC_ESHAPE, SPEC_EDTYPE, SPEC_ENOMEM, SPEC_EHIP = 0, -1, 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecdraft.so")
 
 EXPORTS = ["spec_create", "spec_destroy", "spec_draft", "spec_draft_static", "spec_draft_dynamic", "spec_verify", "spec_verify_dynamic", "spec_head_logp", "spec_model_scalars",
-           "spec_profile_enable", "spec_profile_read", "spec_copy_probe", "spec_set_fused", "spec_fused_timeout", "spec_fused_phase_us", "spec_tree_metadata", "spec_advance", "spec_plan_contraction", "spec_last_error", "spec_version"]
+           "spec_profile_enable", "spec_profile_read", "spec_copy_probe", "spec_tree_metadata", "spec_advance", "spec_plan_contraction", "spec_last_error", "spec_version"]
 
 
 class SpecError(RuntimeError):
@@ -100,12 +100,6 @@ def lib() -> C.CDLL:
         l.spec_profile_read.argtypes = [C.c_void_p, C.POINTER(spec_launch_record_t), C.c_int32, C.POINTER(C.c_int32)]
         l.spec_plan_contraction.restype = C.c_int
         l.spec_plan_contraction.argtypes = [C.c_int32] * 6 + [C.POINTER(spec_plan_t)]
-        l.spec_set_fused.restype = C.c_int
-        l.spec_set_fused.argtypes = [C.c_void_p, C.c_int32]
-        l.spec_fused_timeout.restype = C.c_int
-        l.spec_fused_timeout.argtypes = [C.c_void_p, C.c_int64]
-        l.spec_fused_phase_us.restype = C.c_int
-        l.spec_fused_phase_us.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)]
         l.spec_tree_metadata.restype = C.c_int
         l.spec_tree_metadata.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 7
         l.spec_advance.restype = C.c_int
@@ -415,22 +409,6 @@ def spec_profile_read(model: SpecModel, cap: int = 65536):
     n = C.c_int32()
     _check(lib().spec_profile_read(model.handle, buf, cap, C.byref(n)))
     return [dict(kernel=r.kernel, rows=r.rows, weight_rows=r.weight_rows, k=r.k, ms=r.ms) for r in buf[:n.value]]
-
-
-def spec_set_fused(model: SpecModel, enable: bool) -> None:
-    _check(lib().spec_set_fused(model.handle, 1 if enable else 0))
-
-
-def spec_fused_timeout(model: SpecModel, microseconds: int) -> None:
-    _check(lib().spec_fused_timeout(model.handle, int(microseconds)))
-
-
-def spec_fused_phase_us(model: SpecModel):
-    """Phase durations (us) of the last fused draft launch; [] if none has run."""
-    buf = (C.c_float * 32)()
-    n = C.c_int32()
-    _check(lib().spec_fused_phase_us(model.handle, buf, 32, C.byref(n)))
-    return [float(x) for x in buf[:n.value]]
 
 
 def spec_tree_metadata(cand_tokens: torch.Tensor, node_tok: torch.Tensor, node_parent: torch.Tensor,

@@ -25,7 +25,6 @@ SOURCES = [
     "kernels_f32.hip",
     "kernels_head_skinny.hip",
     "kernels_head_gemm.hip",
-    "kernels_draft_fused.hip",
     "kernels_tree_meta.hip",
 ]
 

@@ -5,11 +5,10 @@
 
 namespace specdraft {
 
-// Stores of results that OTHER workgroups of the same launch read after a device-wide
-// barrier (the whole-draft kernel): agent-scope stores are written through to memory,
-// past the writer's own XCD-local L2, so that a reader on another XCD finds them without
-// any cache having to be written back as a whole.  In the stand-alone kernels they cost
-// nothing extra (the data is a few KB).
+// Stores of results that ANOTHER workgroup of the same launch reads (the closing step of a
+// streaming launch): agent-scope stores are written through to memory, past the writer's own
+// XCD-local L2, so that a reader on another XCD finds them without any cache having to be
+// written back as a whole (an L2-wide write-back per workgroup costs more than the launch).
 __device__ __forceinline__ void store_agent(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -39,10 +38,9 @@ __device__ __forceinline__ float erf_as(float x) {
   return copysignf(r, x);
 }
 
-// threadIdx.x as a value the optimiser cannot look through.  The phase bodies that the
-// fused whole-draft kernel runs in a loop derive every per-thread index from it, so
-// that the compiler does not hoist those computations out of the loop and keep dozens
-// of registers alive across all phases.
+// threadIdx.x as a value the optimiser cannot look through: bodies that are inlined into several
+// kernels derive every per-thread index from it, so that the compiler does not hoist those
+// computations across the bodies and keep dozens of registers alive.
 __device__ __forceinline__ int opaque_tid() {
   int t = threadIdx.x;
   asm volatile("" : "+v"(t));

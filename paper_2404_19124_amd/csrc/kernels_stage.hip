@@ -11,7 +11,7 @@ namespace specdraft {
 template <bool BF16, int NCH>
 __global__ __launch_bounds__(256) void stage_kernel(StageJob j) {
   __shared__ float lds[64];
-  stage_row<BF16, NCH, 256, false>(j, blockIdx.x, lds);
+  stage_row<BF16, NCH, 256>(j, blockIdx.x, lds);
 }
 
 template <bool BF16>

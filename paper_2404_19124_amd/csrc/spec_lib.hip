@@ -52,6 +52,7 @@ struct Workspace {
   float* lse = nullptr;
   float* logits = nullptr;    // f32 path and spec_head_logp: materialised rows
   int64_t logits_rows = 0;
+  unsigned* tail_counters = nullptr;  // kTailCounterWords words, ZERO between launches (see TailJob)
 };
 
 struct spec_model {
@@ -89,23 +90,6 @@ struct spec_model {
   std::vector<hipEvent_t> ev;   // 2 per record slot
   std::vector<Rec> rec;
   int prof_cap = 0, prof_n = 0;
-  // whole-draft kernel: words of its device-wide barrier (monotone: the host counts the
-  // barriers completed so far), failure flag in host-visible memory,
-  // phase time stamps of the last launch
-  unsigned* barrier = nullptr;
-  unsigned barrier_value = 0;
-  int* fail_host = nullptr;
-  int* fail_dev = nullptr;
-  unsigned long long* clocks = nullptr;
-  int clocks_n = 0;
-  bool fused_enabled = false;  // opt-in (spec_set_fused): measured slower than separate launches
-  unsigned long long fused_timeout_ticks = 200000000ull;  // 2 s of the 100 MHz wall clock
-  // Workspace of the whole-draft kernel, one set PER STAGE: inside one launch a buffer
-  // that other workgroups read is written once and never read before that, so no cache
-  // can hold a stale line of it (see kernels_draft_fused.hip)
-  void* fstates[kMaxStages] = {};
-  float* fpz[kMaxStages] = {};
-  Partials fpart[kMaxStages] = {};
 };
 
 static void free_model(spec_model* m) {
@@ -113,7 +97,6 @@ static void free_model(spec_model* m) {
   for (hipEvent_t e : m->ev) (void)hipEventDestroy(e);
   for (void* p : m->owned)
     if (p) (void)hipFree(p);
-  if (m->fail_host) (void)hipHostFree(m->fail_host);
   for (int q = 0; q < spec_model::kDynSlots; ++q) {
     if (m->dyn_host[q]) (void)hipHostFree(m->dyn_host[q]);
     if (m->dyn_ev[q]) (void)hipEventDestroy(m->dyn_ev[q]);
@@ -344,29 +327,14 @@ extern "C" spec_status_t spec_create(const spec_config_t* cfg, const spec_weight
   m->ws.logits_rows = m->bf16 ? 0 : max_rows;
   TRY_FREE(dev_alloc(m, &m->ws.logits, (size_t)m->ws.logits_rows * V * 4));
 
-  if (m->bf16) {
-    const size_t slots = (size_t)16 * skinny_grid(m->n_cu);
-    for (int i = 0; i < n; ++i) {
-      TRY_FREE(dev_alloc(m, &m->fstates[i], (size_t)16 * D * 2));
-      TRY_FREE(dev_alloc(m, &m->fpz[i], (size_t)16 * D * 4));
-      TRY_FREE(dev_alloc(m, &m->fpart[i].m, slots * 4));
-      TRY_FREE(dev_alloc(m, &m->fpart[i].s, slots * 4));
-      TRY_FREE(dev_alloc(m, &m->fpart[i].val, slots * kMaxTopK * 4));
-      TRY_FREE(dev_alloc(m, &m->fpart[i].idx, slots * kMaxTopK * 4));
-    }
-  }
   m->dyn_ints = 2 * sum_rows + (int64_t)cfg->max_batch * (2 * n + 2) + 64;
   TRY_FREE(dev_alloc(m, &m->dyn_dev, (size_t)m->dyn_ints * 4));
   for (int q = 0; q < spec_model::kDynSlots; ++q) {
     HIP_TRY_FREE(hipHostMalloc(reinterpret_cast<void**>(&m->dyn_host[q]), (size_t)m->dyn_ints * 4, hipHostMallocDefault));
     HIP_TRY_FREE(hipEventCreateWithFlags(&m->dyn_ev[q], hipEventDisableTiming));
   }
-  TRY_FREE(dev_alloc(m, &m->barrier, fused_barrier_bytes()));
-  HIP_TRY_FREE(hipMemsetAsync(m->barrier, 0, fused_barrier_bytes(), stream));
-  TRY_FREE(dev_alloc(m, &m->clocks, (2 * kMaxStages + 4) * sizeof(unsigned long long)));
-  HIP_TRY_FREE(hipHostMalloc(reinterpret_cast<void**>(&m->fail_host), 64, hipHostMallocMapped));
-  *m->fail_host = 0;
-  HIP_TRY_FREE(hipHostGetDevicePointer(reinterpret_cast<void**>(&m->fail_dev), m->fail_host, 0));
+  TRY_FREE(dev_alloc(m, &m->ws.tail_counters, (size_t)kTailCounterWords * 4));
+  HIP_TRY_FREE(hipMemsetAsync(m->ws.tail_counters, 0, (size_t)kTailCounterWords * 4, stream));
 
   HIP_TRY_FREE(hipStreamSynchronize(stream));
 #undef TRY_FREE
@@ -496,32 +464,6 @@ extern "C" spec_status_t spec_copy_probe(const void* src, void* dst, int64_t byt
   return SPEC_OK;
 }
 
-extern "C" spec_status_t spec_set_fused(spec_model_t* m, int32_t enable) {
-  if (!m) return fail(SPEC_EINVAL, "model is NULL");
-  m->fused_enabled = enable != 0;
-  return SPEC_OK;
-}
-
-extern "C" spec_status_t spec_fused_timeout(spec_model_t* m, int64_t microseconds) {
-  if (!m) return fail(SPEC_EINVAL, "model is NULL");
-  if (microseconds < 0 || microseconds > 60000000) return fail(SPEC_EINVAL, "microseconds outside [0, 60 s]");
-  m->fused_timeout_ticks = (unsigned long long)microseconds * 100ull;
-  return SPEC_OK;
-}
-
-extern "C" spec_status_t spec_fused_phase_us(spec_model_t* m, float* us, int32_t cap, int32_t* n) {
-  if (!m || !us || !n) return fail(SPEC_EINVAL, "a required pointer is NULL");
-  unsigned long long t[2 * kMaxStages + 4] = {0};
-  const int cnt = m->clocks_n;
-  *n = 0;
-  if (cnt < 2) return SPEC_OK;
-  HIP_TRY(hipMemcpy(t, m->clocks, (size_t)cnt * sizeof(t[0]), hipMemcpyDeviceToHost));
-  int w = 0;
-  for (int i = 0; i + 1 < cnt && w < cap; ++i) us[w++] = (float)((double)(t[i + 1] - t[i]) * 0.01);  // 100 MHz
-  *n = w;
-  return SPEC_OK;
-}
-
 // One contraction of R state rows against head[stage] (top-k partials, or raw
 // logits into out_head) and, if proj_stage >= 0, against proj[proj_stage]
 // (stored to out_proj).  Returns the number of parts per row it produced.
@@ -556,17 +498,16 @@ static HeadJob make_head_job(const spec_model* m, const Workspace& ws, int stage
 
 static spec_status_t run_contraction(spec_model* m, const Workspace& ws, int stage, int proj_stage, const void* b_src, bool b_rowmajor,
                                      int b_ld, int R, int k_top, float* out_head, float* out_proj, int* nparts,
-                                     hipStream_t st, int* proj_parts = nullptr, const FoldJob* fold = nullptr) {
+                                     hipStream_t st, int* proj_parts = nullptr, const TailJob* tail = nullptr) {
   if (proj_parts) *proj_parts = 1;
   HeadJob job = make_head_job(m, ws, stage, proj_stage, b_src, b_rowmajor, b_ld, R, k_top, out_head, out_proj);
   const int K = b_ld;
-  if (fold && !skinny_fits(R, job.kt)) return fail(SPEC_ESHAPE, "internal: folded stage on a contraction of %d rows", R);
-  if (fold) job.fold = *fold;
+  if (tail && !skinny_fits(R, job.kt)) return fail(SPEC_ESHAPE, "internal: closing step on a contraction of %d rows", R);
   if (skinny_fits(R, job.kt)) {
     job.nparts = skinny_grid(m->n_cu);
     *nparts = job.nparts;
     const int slot = prof_slot(m, 0, R, job.n_head + job.n_proj, K);
-    HIP_TRY(launch_head_skinny(job, m->n_cu, st, EV0(slot), EV1(slot)));
+    HIP_TRY(launch_head_skinny(job, tail, m->n_cu, st, EV0(slot), EV1(slot)));
     return SPEC_OK;
   }
   GemmPlan pl = plan_gemm(R, k_top, job.n_head, job.n_proj, job.kt, m->n_cu);
@@ -624,7 +565,7 @@ static spec_status_t check_draft(const spec_model_t* m, const void* state, const
 
 // One draft (arguments already checked) with the workspace `ws`: the model's own, or one carved
 // from the static scratch array.
-static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, bool may_fuse, const void* state,
+static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, const void* state,
                                 const int32_t* last_tok, int32_t batch, const int32_t* top_k, int32_t B,
                                 int32_t* cand_tokens, float* cand_scores, int32_t* cand_leaf, const spec_debug_t* dbg,
                                 void* hip_stream, const DynPlan* dyn = nullptr) {
@@ -648,18 +589,6 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, bool may_f
       ro += r;
       r *= top_k[i];
     }
-  }
-
-  if (*m->fail_host) {
-    // an earlier whole-draft launch gave up at its device-wide barrier: its results were
-    // invalid, and the arrival counter is in an unknown state
-    *m->fail_host = 0;
-    m->fused_enabled = false;
-    // (the counters restart from zero, should the caller switch the mode on again)
-    m->barrier_value = 0;
-    (void)launch_fill_u32(m->barrier, (int64_t)(fused_barrier_bytes() / 4), 0u, st);
-    return fail(SPEC_EHIP, "an earlier fused draft launch timed out at its device-wide barrier (workgroups not "
-                           "co-resident); its results are invalid; further drafts use separate launches");
   }
 
   auto stage_job = [&](int i, int nparts) {
@@ -723,41 +652,35 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, bool may_f
     return tj;
   };
 
-  // every stage at most 16 rows (batch 1 with the paper's trees): the whole draft in one launch
-  const int grid = skinny_grid(m->n_cu);
-  bool fused = may_fuse && !dyn && m->bf16 && m->fused_enabled && R[n - 1] <= 16 && batch <= 16 &&
-               fused_fits((int)R[n - 1] > batch ? (int)R[n - 1] : batch, E / 32, D / 32, grid);
-  if (fused) {
-    FusedJob fj;
-    memset(&fj, 0, sizeof(fj));
-    fj.n = n;
-    fj.batch = batch;
-    fj.n_wg = grid;
-    fj.barrier_base = m->barrier_value;
-    fj.barrier = m->barrier;
-    fj.fail_flag = m->fail_dev;
-    fj.clocks = m->clocks;
-    fj.timeout_ticks = m->fused_timeout_ticks;
-    fj.head[0] = make_head_job(m, ws, -1, 0, state, true, E, batch, 0, nullptr, m->fpz[0]);
-    fj.head[0].nparts = grid;
-    int64_t sum_rows = batch;
+  // Every contraction of the call on the streaming kernel (at most 16 rows per stage: batch 1 with the
+  // paper's trees): no stage or tree launches; each streaming launch closes with the next stage's rows
+  // (the last one with the tree step), computed by its last workgroup.
+  bool tails = m->bf16 && !dyn && ws.tail_counters && skinny_fits(batch, E / 32) && tail_fits(batch, D);
+  for (int i = 0; tails && i < n; ++i) tails = skinny_fits((int)R[i], D / 32) && tail_fits((int)R[i], D);
+  if (tails) {
+    const int grid = skinny_grid(m->n_cu);
+    int nparts = 0;
+    TailJob tj;
+    memset(&tj, 0, sizeof(tj));
+    tj.kind = 1;
+    tj.counters = ws.tail_counters;
+    tj.stage = stage_job(0, 0);
+    spec_status_t s = run_contraction(m, ws, -1, 0, state, true, E, batch, 0, nullptr, ws.pz[0], &nparts, st, nullptr, &tj);
+    if (s != SPEC_OK) return s;
     for (int i = 0; i < n; ++i) {
-      fj.stage[i] = stage_job(i, grid);
-      fj.stage[i].pz = m->fpz[i];
-      fj.stage[i].state_out = m->fstates[i];
-      if (i > 0) fj.stage[i].part = m->fpart[i - 1];
-      fj.head[i + 1] = make_head_job(m, ws, i, i + 1 < n ? i + 1 : -1, m->fstates[i], false, D, (int)R[i], top_k[i],
-                                     nullptr, i + 1 < n ? m->fpz[i + 1] : nullptr);
-      fj.head[i + 1].part = m->fpart[i];
-      fj.head[i + 1].nparts = grid;
-      sum_rows += R[i];
+      memset(&tj, 0, sizeof(tj));
+      tj.counters = ws.tail_counters;
+      if (i + 1 < n) {
+        tj.kind = 1;
+        tj.stage = stage_job(i + 1, grid);
+      } else {
+        tj.kind = 2;
+        tj.tree = tree_job(grid);
+      }
+      s = run_contraction(m, ws, i, i + 1 < n ? i + 1 : -1, ws.states, false, D, (int)R[i], top_k[i], nullptr,
+                          ws.pz[(i + 1) & 1], &nparts, st, nullptr, &tj);
+      if (s != SPEC_OK) return s;
     }
-    fj.tree = tree_job(grid);
-    fj.tree.part = m->fpart[n - 1];
-    const int slot = prof_slot(m, 4, (int)sum_rows, n * V + n * D, D);
-    HIP_TRY(launch_draft_fused(fj, (int)R[n - 1] > batch ? (int)R[n - 1] : batch, st, EV0(slot), EV1(slot)));
-    m->barrier_value += (unsigned)kFusedBarriers(n);
-    m->clocks_n = 2 * n + 4;
   } else {
     int nparts = 1, pz0_parts = 1;
     const bool any_rows = R[0] > 0;   // (per-sequence trees: every sequence may have speculation switched off)
@@ -777,25 +700,11 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, bool may_f
         sj.pz_parts = pz0_parts;
         sj.pz_part_stride = (int64_t)batch * D;
       }
-      // First stage of one or two sequences: its rows (token = the last sampled one, no merge) are
-      // computed inside the head's streaming kernel instead of by a launch of their own.
-      FoldJob fold;
-      memset(&fold, 0, sizeof(fold));
-      const bool folded = i == 0 && m->bf16 && !dbg && !dyn && skinny_fits((int)R[0], D / 32) && (int)R[0] <= skinny_fold_rows(D);
-      if (folded) {
-        fold.enabled = 1;
-        fold.D = D; fold.V = V;
-        fold.pz = sj.pz; fold.pz_parts = sj.pz_parts > 0 ? sj.pz_parts : 1; fold.pz_part_stride = sj.pz_part_stride;
-        fold.tok = last_tok;
-        fold.emb = sj.emb; fold.gamma = sj.gamma; fold.beta = sj.beta;
-        fold.w_s = sj.w_s; fold.w_e = sj.w_e; fold.eps = sj.eps;
-      } else {
-        HIP_TRY(launch_stage(sj, st));
-      }
+      HIP_TRY(launch_stage(sj, st));
       const int proj_next = i + 1 < n ? i + 1 : -1;
       if (m->bf16) {
         spec_status_t s = run_contraction(m, ws, i, proj_next, ws.states, false, D, (int)R[i], top_k[i], nullptr,
-                                          ws.pz[(i + 1) & 1], &nparts, st, nullptr, folded ? &fold : nullptr);
+                                          ws.pz[(i + 1) & 1], &nparts, st);
         if (s != SPEC_OK) return s;
       } else {
         const float* sf = static_cast<const float*>(ws.states);
@@ -824,7 +733,7 @@ extern "C" spec_status_t spec_draft(spec_model_t* m, const void* state, const in
                                     int32_t* cand_leaf, const spec_debug_t* dbg, void* hip_stream) {
   spec_status_t s = check_draft(m, state, last_tok, batch, top_k, B, cand_tokens, cand_scores, cand_leaf);
   if (s != SPEC_OK) return s;
-  return draft_impl(m, m->ws, true, state, last_tok, batch, top_k, B, cand_tokens, cand_scores, cand_leaf, dbg,
+  return draft_impl(m, m->ws, state, last_tok, batch, top_k, B, cand_tokens, cand_scores, cand_leaf, dbg,
                     hip_stream);
 }
 
@@ -918,7 +827,7 @@ extern "C" spec_status_t spec_draft_dynamic(spec_model_t* m, const void* state, 
     dp.rank[i] = m->dyn_dev + r_at[i];
   }
   dp.seq_desc = m->dyn_dev + d_at;
-  return draft_impl(m, m->ws, false, state, last_tok, batch, kw, 1, cand_tokens, cand_scores, cand_leaf, dbg, hip_stream,
+  return draft_impl(m, m->ws, state, last_tok, batch, kw, 1, cand_tokens, cand_scores, cand_leaf, dbg, hip_stream,
                     &dp);
 }
 
@@ -944,6 +853,9 @@ static spec_status_t carve_static(const spec_model* m, unsigned char* base, int 
     if (used > (size_t)SPEC_STATIC_SCRATCH_BYTES) fits = false;
     return p;
   };
+  // (first, at a fixed place: the closing-step counters, zero when the library is loaded and zero again after
+  // every launch that uses them)
+  ws->tail_counters = reinterpret_cast<unsigned*>(take((size_t)kTailCounterWords * 4));
   const int64_t rows16 = (max_rows + 15) / 16 * 16, batch16 = ((int64_t)batch + 15) / 16 * 16;
   const int64_t pz_rows = max_parent > (int64_t)kMaxKSplit * batch ? max_parent : (int64_t)kMaxKSplit * batch;
   // parts per row: one per workgroup of the streaming kernel when every stage has at most 16 rows,
@@ -982,7 +894,7 @@ extern "C" spec_status_t spec_draft_static(spec_model_t* m, const void* state, c
     return fail(SPEC_EINVAL, "the model lives on device %d, the current device is %d", m->device, dev);
   s = carve_static(m, base, batch, top_k, &ws);
   if (s != SPEC_OK) return s;
-  return draft_impl(m, ws, false, state, last_tok, batch, top_k, B, cand_tokens, cand_scores, cand_leaf, nullptr,
+  return draft_impl(m, ws, state, last_tok, batch, top_k, B, cand_tokens, cand_scores, cand_leaf, nullptr,
                     hip_stream);
 }
 

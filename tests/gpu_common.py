@@ -33,9 +33,8 @@ def tables_to_numpy(step: Step):
 
 def run_workload(wl: W.Workload, ln_affine: str = "identity", gen_device: str = "cuda",
                  sample_seqs: Optional[Sequence[int]] = None, w_s: float = -1.0, w_e: float = -1.0,
-                 check_verify: bool = True, tied: bool = False, fused: Optional[bool] = None):
-    """Returns (report, step, oracle draft, oracle verify).  fused: None = the library's
-    choice, True / False = spec_set_fused before the draft."""
+                 check_verify: bool = True, tied: bool = False):
+    """Returns (report, step, oracle draft, oracle verify)."""
     t0 = time.time()
     log("workload %s: E=%d D=%d V=%d n=%d k=%s B=%d batch=%d dtype=%s seed=%d"
         % (wl.name, wl.emb_dim, wl.inner_dim, wl.vocab, wl.n_predict, wl.top_k, wl.B, wl.batch, wl.weight_dtype, wl.seed))
@@ -50,8 +49,6 @@ def run_workload(wl: W.Workload, ln_affine: str = "identity", gen_device: str = 
     state_d, last_d = state.cuda(), last.cuda()
 
     step = Step(wl, w_dev, debug=True, state_weight=w_s, emb_weight=w_e)
-    if fused is not None:
-        B.spec_set_fused(step.model, fused)
     step.draft(state_d, last_d)
     torch.cuda.synchronize()
     log("  HIP draft done (%.1fs)" % (time.time() - t0))
@@ -98,10 +95,9 @@ def run_workload(wl: W.Workload, ln_affine: str = "identity", gen_device: str = 
     for note in rep.notes[:5]:
         log("    " + note)
 
-    # The debug outputs above are not free of side effects on the launch sequence (with them the first
-    # stage always gets a launch of its own): the configuration the benchmark times is the one WITHOUT
-    # them.  It must choose the same candidates, and its scores are held to the oracle's leaf scores.
-    if fused is None and w_s < 0 and not tied:
+    # The configuration the benchmark times is the one WITHOUT debug outputs.  It must choose the same
+    # candidates, and its scores are held to the oracle's leaf scores.
+    if w_s < 0 and not tied:
         plain = Step(wl, w_dev)
         plain.draft(state_d, last_d)
         torch.cuda.synchronize()

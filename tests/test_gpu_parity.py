@@ -95,72 +95,40 @@ def test_small_bf16_shapes(case):
     assert rep.rows_exempt <= 1
 
 
-# Shapes the one-launch draft takes (every stage <= 16 rows, E == D a multiple of 512 up to 4096).
-FUSED_BF16 = [
-    ("fused_d512_rows_1_5_15", 512, 512, 1000, 3, (5, 3, 2), 10, 1),    # the paper's tree shape, ragged vocabulary
-    ("fused_d1024_b2", 1024, 1024, 2049, 3, (2, 2, 2), 8, 2),           # two sequences: 2, 4, 8 rows
-    ("fused_d2048_k8", 2048, 2048, 777, 2, (8, 8), 64, 2),              # 16 rows, widest top-k, group merge in the tree
-    ("fused_d512_chain_n7", 512, 512, 500, 7, (1,) * 7, 1, 2),          # k = 1 chain, 15 barriers
-    ("fused_d3072_b1", 3072, 3072, 640, 2, (6, 2), 12, 1),
+# Every stage at most 16 rows: the streaming kernel with its closing step (the launch's last workgroup
+# computes the next stage's rows / the tree step) - widths that take one and two chunks per thread there,
+# every merge width, several sequences, a 7-stage chain.
+CLOSING_STEP_BF16 = [
+    ("tail_d512_rows_1_5_15", 512, 512, 1000, 3, (5, 3, 2), 10, 1),    # the paper's tree shape, ragged vocabulary
+    ("tail_d1024_b2", 1024, 1024, 2049, 3, (2, 2, 2), 8, 2),           # two sequences: 2, 4, 8 rows
+    ("tail_d2048_k8", 2048, 2048, 777, 2, (8, 8), 64, 2),              # 16 rows, widest top-k: group merges
+    ("tail_d512_chain_n7", 512, 512, 500, 7, (1,) * 7, 1, 2),          # k = 1 chain
+    ("tail_d3072_b1", 3072, 3072, 640, 2, (6, 2), 12, 1),              # two chunks per thread, merge width 6
+    ("tail_d1536_b1", 512, 1536, 700, 2, (8, 2), 16, 1),               # E != D, 192 chunks per row
+    ("tail_d4096_b2_chain", 512, 4096, 300, 4, (1,) * 4, 1, 2),        # the 7B width
+    ("tail_d512_b3", 512, 512, 1000, 3, (3, 2, 1), 6, 3),              # 3, 9, 18 rows: 18 > 16, the last stage leaves the path
+    ("tail_d4096_rows_16", 4096, 4096, 300, 3, (4, 4, 1), 16, 1),      # 16 rows: four rounds in two passes
+    ("tail_d256_b16", 128, 256, 500, 2, (1, 1), 1, 16),                # 16 sequences: the tree step loops over them
 ]
 
 
-@pytest.mark.parametrize("case", FUSED_BF16, ids=[c[0] for c in FUSED_BF16])
-def test_fused_draft_matches_oracle_and_separate_launches(case):
+@pytest.mark.parametrize("case", CLOSING_STEP_BF16, ids=[c[0] for c in CLOSING_STEP_BF16])
+def test_streaming_launches_with_closing_step(case):
     name, E, D, V, n, top_k, Bc, batch = case
     wl = W.Workload(name, E, D, V, n, top_k, Bc, batch, "bf16", "f32", 0.6, seed=17, emb_std=0.3)
-    rep_f, step_f, od, ov = run_workload(wl, ln_affine="random", gen_device="cpu", fused=True)
-    phases = B.spec_fused_phase_us(step_f.model)
-    assert len(phases) == 2 * n + 3, "the fused launch did not run: %s" % phases
-    assert all(0.0 <= p < 1e6 for p in phases), phases
-    rep_s, step_s, _, _ = run_workload(wl, ln_affine="random", gen_device="cpu", fused=False)
-    assert B.spec_fused_phase_us(step_s.model) == []
-    # same arithmetic in the same order: the two modes agree bit for bit
-    for a, b in ((step_f.cand_tokens, step_s.cand_tokens), (step_f.cand_scores, step_s.cand_scores),
-                 (step_f.cand_leaf, step_s.cand_leaf)):
-        assert torch.equal(a, b)
-    for key in ("stage_state", "topk_tok", "topk_logp", "row_lse"):
-        assert torch.equal(step_f.dbg[key], step_s.dbg[key]), key
-    # a second call on the same model (the barrier counter carries on)
-    step_f.cand_tokens.zero_()
+    rep, step, od, ov = run_workload(wl, ln_affine="random", gen_device="cpu")
+    assert rep.rows_checked + rep.rows_skipped_below_exempt == sum(wl.rows())
+    assert rep.rows_exempt <= 1
+    # repeated calls on the same model (the closing step's counters return to zero by themselves)
     gen = W.make_generator(wl.seed, "cpu")
     W.make_speculator(wl, gen, device="cpu", ln_affine="random")
     state, last = W.make_draft_inputs(wl, gen, device="cpu")
+    want = step.cand_tokens.clone()
     for _ in range(3):
-        step_f.draft(state.cuda(), last.cuda())
+        step.cand_tokens.zero_()
+        step.draft(state.cuda(), last.cuda())
     torch.cuda.synchronize()
-    assert torch.equal(step_f.cand_tokens, step_s.cand_tokens)
-
-
-def test_fused_draft_barrier_timeout_is_reported_and_the_model_recovers():
-    """A barrier wait bound of zero makes the fused launch give up (all workgroups leave
-    normally); the next draft reports it, the mode switches off and later drafts are right."""
-    wl = W.Workload("fused_timeout", 512, 512, 1000, 3, (5, 3, 2), 10, 1, "bf16", "f32", 0.6, seed=17, emb_std=0.3)
-    rep, step, od, _ = run_workload(wl, ln_affine="random", gen_device="cpu", fused=False)
-    good = step.cand_tokens.clone()
-    gen = W.make_generator(wl.seed, "cpu")
-    W.make_speculator(wl, gen, device="cpu", ln_affine="random")
-    state, last = W.make_draft_inputs(wl, gen, device="cpu")
-    state, last = state.cuda(), last.cuda()
-    B.spec_set_fused(step.model, True)
-    B.spec_fused_timeout(step.model, 0)
-    step.draft(state, last)            # gives up at its first incomplete barrier
-    torch.cuda.synchronize()
-    with pytest.raises(B.SpecError) as err:
-        step.draft(state, last)
-    assert "barrier" in str(err.value)
-    step.cand_tokens.zero_()
-    step.draft(state, last)            # separate launches from now on
-    torch.cuda.synchronize()
-    assert torch.equal(step.cand_tokens, good)
-    B.spec_fused_timeout(step.model, 2000000)
-    B.spec_set_fused(step.model, True)  # switched on again: the barrier restarts from zero
-    step.cand_tokens.zero_()
-    step.draft(state, last)
-    step.draft(state, last)
-    torch.cuda.synchronize()
-    assert torch.equal(step.cand_tokens, good)
-    assert len(B.spec_fused_phase_us(step.model)) == 2 * wl.n_predict + 3
+    assert torch.equal(step.cand_tokens, want)
 
 
 SMALL_F32 = [
@@ -316,39 +284,6 @@ def test_draft_and_verify_replay_from_a_hip_graph(batch):
             # eager work of the program between the replays
             step.draft(inputs[rep][0], inputs[rep][1])
             torch.cuda.synchronize()
-    step.close()
-
-
-FOLD_CASES = [
-    # name, E, D, V, n, top_k, B, batch: one or two sequences with D a multiple of 512 take the first stage
-    # inside the first head's launch when no debug output is asked for
-    ("fold_d512_b1", 512, 512, 1000, 3, (5, 3, 2), 10, 1),
-    ("fold_d512_b2", 1024, 512, 2049, 3, (4, 2, 2), 8, 2),       # two rows in one round
-    ("fold_d1536_b1", 512, 1536, 700, 2, (8, 2), 16, 1),         # 192 chunks: 5 rows would fit a round, 1 used
-    ("fold_d4096_b2_chain", 512, 4096, 300, 4, (1,) * 4, 1, 2),  # the 7B width, two rows = the round's capacity
-    ("fold_d512_b3", 512, 512, 1000, 3, (3, 2, 2), 6, 3),        # 64 chunks per row: 16 rows fit a round, 3 used
-]
-
-
-@pytest.mark.parametrize("case", FOLD_CASES, ids=[c[0] for c in FOLD_CASES])
-def test_first_stage_inside_the_head_launch_matches_the_stage_kernel_and_the_oracle(case):
-    name, E, D, V, n, top_k, Bc, batch = case
-    wl = W.Workload(name, E, D, V, n, top_k, Bc, batch, "bf16", "f32", 0.6, seed=21, emb_std=0.3)
-    # debug outputs force the stage kernel: this run is compared with the oracle table by table
-    rep, step_dbg, od, ov = run_workload(wl, ln_affine="random", gen_device="cpu", check_verify=False)
-    assert rep.rows_exempt <= 1
-    gen = W.make_generator(wl.seed, "cpu")
-    w = W.make_speculator(wl, gen, device="cpu", ln_affine="random")
-    state, last = W.make_draft_inputs(wl, gen, device="cpu")
-    step = Step(wl, {k: [t.cuda() for t in v] for k, v in w.items()})      # no debug: the folded path
-    step.draft(state.cuda(), last.cuda())
-    torch.cuda.synchronize()
-    # the two paths round the same fp32 arithmetic to bf16 states; block sums differ in order by an ulp at most
-    assert torch.equal(step.cand_tokens, step_dbg.cand_tokens)
-    assert torch.equal(step.cand_leaf, step_dbg.cand_leaf)
-    assert (step.cand_scores - step_dbg.cand_scores).abs().max().item() < 2e-3
-    assert np.array_equal(step.cand_tokens.cpu().numpy(), od.cand_tokens) or rep.rows_exempt > 0
-    assert np.abs(step.cand_scores.cpu().numpy() - od.cand_scores).max() < 2e-2
     step.close()
 
 

@@ -33,7 +33,7 @@ def _both(step, state, last, top_k, Bc):
 
 CASES = [
     # name, E, D, V, n, top_k, B, batch, dtype; second call: (batch2, top_k2, B2)
-    ("skinny_fold_d512", 512, 512, 1000, 3, (5, 3, 2), 10, 1, "bf16", (1, (2, 3, 1), 4)),
+    ("skinny_d512", 512, 512, 1000, 3, (5, 3, 2), 10, 1, "bf16", (1, (2, 3, 1), 4)),
     ("skinny_b3", 128, 192, 1000, 3, (4, 3, 1), 9, 3, "bf16", (2, (2, 2, 1), 3)),
     ("dense_b7", 256, 128, 2049, 3, (5, 3, 2), 16, 7, "bf16", (3, (5, 2, 2), 7)),
     ("dense_b40_long_e", 1024, 128, 300, 2, (3, 2), 6, 40, "bf16", (17, (3, 1), 2)),
