@@ -5,20 +5,6 @@
 
 namespace specdraft {
 
-// Stores of results that ANOTHER workgroup of the same launch reads (the closing step of a
-// streaming launch): agent-scope stores are written through to memory, past the writer's own
-// XCD-local L2, so that a reader on another XCD finds them without any cache having to be
-// written back as a whole (an L2-wide write-back per workgroup costs more than the launch).
-__device__ __forceinline__ void store_agent(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void store_agent(int32_t* p, int32_t v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void store_agent(uint64_t* p, uint64_t v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 // erf by the rational approximation 7.1.26 of Abramowitz and Stegun,
 //   erf(x) = 1 - (a1 t + ... + a5 t^5) exp(-x^2),  t = 1 / (1 + p x),  x >= 0,
 // absolute error <= 1.5e-7 analytically, 6e-7 evaluated in float32: a dozen
@@ -38,9 +24,9 @@ __device__ __forceinline__ float erf_as(float x) {
   return copysignf(r, x);
 }
 
-// threadIdx.x as a value the optimiser cannot look through: bodies that are inlined into several
-// kernels derive every per-thread index from it, so that the compiler does not hoist those
-// computations across the bodies and keep dozens of registers alive.
+// threadIdx.x as a value the optimiser cannot look through: device bodies that are inlined into
+// larger kernels derive every per-thread index from it, so that the compiler does not hoist those
+// computations and keep dozens of registers alive across the whole kernel.
 __device__ __forceinline__ int opaque_tid() {
   int t = threadIdx.x;
   asm volatile("" : "+v"(t));

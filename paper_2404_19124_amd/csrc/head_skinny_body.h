@@ -54,15 +54,92 @@ __device__ __forceinline__ void skinny_prefetch(const HeadJob& p, int wg, int G,
   }
 }
 
-// AGENT: the results are read by another workgroup of the SAME launch (the closing step, see TailJob)
-// and are stored at agent scope (written through); a launch without a closing step stores plainly.
-template <bool AGENT, typename T>
-__device__ __forceinline__ void skinny_put(T* p, T v) {
-  if (AGENT) store_agent(p, v);
-  else *p = v;
+// The folded first stage (FoldJob): rows of D / 8 eight-element chunks, one chunk per thread,
+// NT / (D / 8) rows at a time (the host folds only what fits one round); D is a multiple of 512,
+// so a wave never straddles two rows.  Writes the bf16
+// states into the kernel's LDS layout (slot tg * R + n = row n, columns 8 tg .. 8 tg + 8).
+// `red`: 64 floats of LDS scratch.  Contains workgroup barriers.
+template <int NT>
+__device__ __forceinline__ void fold_states(const HeadJob& p, u32x4* ldsB, float* red) {
+  const FoldJob& f = p.fold;
+  const int tid = opaque_tid(), lane = tid & 63, w = tid >> 6;
+  const int R = p.R, D = f.D, nchunk = D / 8, wpr = nchunk / 64;
+  const int rp = NT / nchunk;  // rows per round
+  const int sub = tid / nchunk, c = tid - sub * nchunk;
+  int buf = 0;
+  for (int r0 = 0; r0 < R; r0 += rp) {
+    const int r = r0 + sub;
+    const bool live = sub < rp && r < R;
+    float z[8], ga[8], be[8];
+    float lsum = 0.f;
+    if (live) {
+      const float* pz = f.pz + (int64_t)r * D + c * 8;
+      float4 p0 = *reinterpret_cast<const float4*>(pz);
+      float4 p1 = *reinterpret_cast<const float4*>(pz + 4);
+      for (int q = 1; q < f.pz_parts; ++q) {
+        const float4 q0 = *reinterpret_cast<const float4*>(pz + q * f.pz_part_stride);
+        const float4 q1 = *reinterpret_cast<const float4*>(pz + q * f.pz_part_stride + 4);
+        p0.x += q0.x; p0.y += q0.y; p0.z += q0.z; p0.w += q0.w;
+        p1.x += q1.x; p1.y += q1.y; p1.z += q1.z; p1.w += q1.w;
+      }
+      const int tok = min(max(f.tok[r], 0), f.V - 1);
+      const uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(f.emb) + (int64_t)tok * D + c * 8);
+      const float4 g0 = *reinterpret_cast<const float4*>(f.gamma + c * 8);
+      const float4 g1 = *reinterpret_cast<const float4*>(f.gamma + c * 8 + 4);
+      const float4 b0 = *reinterpret_cast<const float4*>(f.beta + c * 8);
+      const float4 b1 = *reinterpret_cast<const float4*>(f.beta + c * 8 + 4);
+      ga[0] = g0.x; ga[1] = g0.y; ga[2] = g0.z; ga[3] = g0.w; ga[4] = g1.x; ga[5] = g1.y; ga[6] = g1.z; ga[7] = g1.w;
+      be[0] = b0.x; be[1] = b0.y; be[2] = b0.z; be[3] = b0.w; be[4] = b1.x; be[5] = b1.y; be[6] = b1.z; be[7] = b1.w;
+      const float pzv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+      const uint32_t ew[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const float e = bf16_bits_to_f32((q & 1) ? (ew[q >> 1] >> 16) : (ew[q >> 1] & 0xffffu));
+        z[q] = f.w_s * pzv[q] + f.w_e * e;
+        lsum += z[q];
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) { z[q] = 0.f; ga[q] = 0.f; be[q] = 0.f; }
+    }
+    // per-row sums over the row's wpr waves (two scratch areas per round, two rounds alternate)
+    float* ra = red + buf * 32;
+    float s = wave_sum(lsum);
+    if (lane == 0) ra[w] = s;
+    __syncthreads();
+    float mean = 0.f;
+    for (int q = 0; q < wpr; ++q) mean += ra[min(sub, rp - 1) * wpr + q];
+    mean /= (float)D;
+    float lvar = 0.f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const float d = z[q] - mean;
+      lvar += live ? d * d : 0.f;
+    }
+    s = wave_sum(lvar);
+    if (lane == 0) ra[16 + w] = s;
+    __syncthreads();
+    float var = 0.f;
+    for (int q = 0; q < wpr; ++q) var += ra[16 + min(sub, rp - 1) * wpr + q];
+    var /= (float)D;
+    const float rstd = 1.0f / sqrtf(var + f.eps);
+    if (live) {
+      float sv[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const float y = (z[q] - mean) * rstd * ga[q] + be[q];
+        sv[q] = 0.5f * y * (1.0f + erf_as(y * 0.70710678118654752440f));
+      }
+      u32x4 o;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) o[q] = f32_to_bf16_bits(sv[2 * q]) | (f32_to_bf16_bits(sv[2 * q + 1]) << 16);
+      ldsB[c * R + r] = o;
+    }
+    buf ^= 1;
+  }
 }
 
-template <int NS, int DEPTH, bool EXACT, bool AGENT>
+template <int NS, int DEPTH, bool EXACT>
 __device__ __forceinline__ void skinny_run(const HeadJob& p, int wg, int G, u32x4 (&a)[DEPTH][NS],
                                            unsigned char* smem) {
   const int kt = p.kt, R = p.R;
@@ -87,7 +164,9 @@ __device__ __forceinline__ void skinny_run(const HeadJob& p, int wg, int G, u32x
   };
 
   // ---- states -> LDS, trimmed to R rows: slot (t, g, n) = row n, columns t*32 + g*8 .. +8
-  if (p.b_rowmajor) {
+  if (p.fold.enabled) {
+    fold_states<NT>(p, ldsB, reinterpret_cast<float*>(ldsP));
+  } else if (p.b_rowmajor) {
     for (int n = 0; n < R; ++n) {
       const uint16_t* row = static_cast<const uint16_t*>(p.b_src) + (int64_t)n * p.b_ld;
       for (int tg = tid; tg < kt * 4; tg += NT) ldsB[tg * R + n] = *reinterpret_cast<const u32x4*>(row + tg * 8);
@@ -167,7 +246,7 @@ __device__ __forceinline__ void skinny_run(const HeadJob& p, int wg, int G, u32x
               }
             } else {
               const int d2 = (tile - p.vt_head) * 16 + vi;
-              if (d2 < p.n_proj) skinny_put<AGENT>(&p.out_proj[(int64_t)en * p.ld_proj + d2], sum);
+              if (d2 < p.n_proj) p.out_proj[(int64_t)en * p.ld_proj + d2] = sum;
             }
           }
         }
@@ -209,8 +288,8 @@ __device__ __forceinline__ void skinny_run(const HeadJob& p, int wg, int G, u32x
     s = row16_sum((m > SPEC_NEG_INF) ? s * __expf(m - mx) : 0.f);
     const int64_t slot = (int64_t)row * p.nparts + wg;
     if (row < R && src == 0) {
-      skinny_put<AGENT>(&p.part.m[slot], mx);
-      skinny_put<AGENT>(&p.part.s[slot], s);
+      p.part.m[slot] = mx;
+      p.part.s[slot] = s;
     }
 #pragma unroll
     for (int j = 0; j < kMaxTopK; ++j) {
@@ -225,8 +304,8 @@ __device__ __forceinline__ void skinny_run(const HeadJob& p, int wg, int G, u32x
           hi[kMaxTopK - 1] = kIdxNone;
         }
         if (row < R && src == j) {
-          skinny_put<AGENT>(&p.part.val[slot * p.k_top + j], bv);
-          skinny_put<AGENT>(&p.part.idx[slot * p.k_top + j], bi);
+          p.part.val[slot * p.k_top + j] = bv;
+          p.part.idx[slot * p.k_top + j] = bi;
         }
       }
     }

@@ -43,6 +43,28 @@ struct Partials {
 hipError_t launch_pack_bf16(const void* src, void* dst, int n_rows, int k, bool zero_pad, hipStream_t st);
 
 // ---- contraction, bf16 on the matrix cores --------------------------------
+// Optional prologue of the streaming kernel for the FIRST stage of a draft with one or two
+// sequences: every workgroup computes the stage's state rows itself, straight into its LDS,
+//   state_r = GELU(LayerNorm(w_s * pz[r] + w_e * Emb[tok_r]))  (Sec. 3.1),
+// instead of reading them from a stage kernel's output, which removes a launch from the serial
+// chain of a batch-1 step.  The few KB it reads arrive behind the weight tiles already
+// requested (loads complete in order), i.e. when the weight ring has landed: one such round trip
+// is free, because the stream is bound by HBM and the matrix cores catch up; a chain of them is
+// not (measured: later stages, whose tokens first need a merge and whose rows take several
+// rounds, lose 11-30 us this way and keep their stage kernel).
+struct FoldJob {
+  int enabled;
+  int D, V;
+  const float* pz;           // [R][D] projected states of the base model, as pz_parts partial sums
+  int pz_parts;
+  int64_t pz_part_stride;
+  const int32_t* tok;        // [R] token of every row (the last sampled tokens)
+  const void* emb;           // [V][D] bf16
+  const float* gamma;
+  const float* beta;
+  float w_s, w_e, eps;
+};
+
 struct HeadJob {
   // weights (packed): `n_head` valid rows in `vt_head` tiles, then optionally a
   // second matrix (the next stage's projection) of `n_proj` rows in `vt_proj` tiles.
@@ -67,6 +89,7 @@ struct HeadJob {
   // a projection launched alone may be split along K (GemmPlan::ksplit): part q holds the sum over
   // its K range at out_proj + q * proj_part_stride, and the consumer adds the parts in order
   int64_t proj_part_stride;
+  FoldJob fold;           // streaming kernel only
 };
 
 // Rows <= 16: one persistent workgroup per CU, K split over its 16 waves,
@@ -74,6 +97,10 @@ struct HeadJob {
 bool skinny_fits(int R, int kt);
 int skinny_grid(int n_cu);
 size_t skinny_lds_bytes(int R, int kt);   // dynamic LDS of one workgroup
+int skinny_fold_rows(int D);              // rows a FoldJob may have for inner width D (0: none)
+// ev_start / ev_stop (may be null) receive the kernel's own begin / end timestamps.
+hipError_t launch_head_skinny(const HeadJob& job, int n_cu, hipStream_t st, hipEvent_t ev_start = nullptr,
+                              hipEvent_t ev_stop = nullptr);
 
 // Any number of rows: workgroups of (16*mi state rows) x (64*ni weight rows) tiles, each
 // persistent over one of n_ranges contiguous ranges of the weight-row tiles.  Head
@@ -163,25 +190,6 @@ struct TreeJob {
   int32_t* cand_leaf;
 };
 hipError_t launch_tree(const TreeJob& job, hipStream_t st);
-
-// ---- closing step of a streaming launch (rows <= 16) ------------------------------------------
-// The few KB of dependent work between two heads of a batch-1 draft (merge of the head's partial results,
-// embedding gather, LayerNorm, GELU; after the last head: the tree step) are done by the workgroup of the
-// head's launch that finishes LAST, instead of by a launch of their own: every workgroup counts itself in
-// when its results are stored, and the one that completes the count carries on.
-//   kind 0: none;  1: all rows of `stage` (merging the previous head first, if stage.stage > 0);  2: `tree`
-//   counters: kTailCounterWords words (zero between launches: the closing workgroup resets them)
-constexpr int kTailCounterWords = 17 * 32;   // a root and 16 group counters, each on a 128-byte line of its own
-struct TailJob {
-  int kind;
-  unsigned* counters;
-  StageJob stage;
-  TreeJob tree;
-};
-bool tail_fits(int rows, int D);   // a stage of `rows` rows of width D can be computed by a closing step
-// ev_start / ev_stop (may be null) receive the kernel's own begin / end timestamps.  tail may be null.
-hipError_t launch_head_skinny(const HeadJob& job, const TailJob* tail, int n_cu, hipStream_t st,
-                              hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
 // ---- verify ----------------------------------------------------------------
 // n_cand (dev [batch], may be null = every sequence has B candidates): sequence q has n_cand[q] candidates;

@@ -52,7 +52,6 @@ struct Workspace {
   float* lse = nullptr;
   float* logits = nullptr;    // f32 path and spec_head_logp: materialised rows
   int64_t logits_rows = 0;
-  unsigned* tail_counters = nullptr;  // kTailCounterWords words, ZERO between launches (see TailJob)
 };
 
 struct spec_model {
@@ -333,8 +332,6 @@ extern "C" spec_status_t spec_create(const spec_config_t* cfg, const spec_weight
     HIP_TRY_FREE(hipHostMalloc(reinterpret_cast<void**>(&m->dyn_host[q]), (size_t)m->dyn_ints * 4, hipHostMallocDefault));
     HIP_TRY_FREE(hipEventCreateWithFlags(&m->dyn_ev[q], hipEventDisableTiming));
   }
-  TRY_FREE(dev_alloc(m, &m->ws.tail_counters, (size_t)kTailCounterWords * 4));
-  HIP_TRY_FREE(hipMemsetAsync(m->ws.tail_counters, 0, (size_t)kTailCounterWords * 4, stream));
 
   HIP_TRY_FREE(hipStreamSynchronize(stream));
 #undef TRY_FREE
@@ -498,16 +495,17 @@ static HeadJob make_head_job(const spec_model* m, const Workspace& ws, int stage
 
 static spec_status_t run_contraction(spec_model* m, const Workspace& ws, int stage, int proj_stage, const void* b_src, bool b_rowmajor,
                                      int b_ld, int R, int k_top, float* out_head, float* out_proj, int* nparts,
-                                     hipStream_t st, int* proj_parts = nullptr, const TailJob* tail = nullptr) {
+                                     hipStream_t st, int* proj_parts = nullptr, const FoldJob* fold = nullptr) {
   if (proj_parts) *proj_parts = 1;
   HeadJob job = make_head_job(m, ws, stage, proj_stage, b_src, b_rowmajor, b_ld, R, k_top, out_head, out_proj);
   const int K = b_ld;
-  if (tail && !skinny_fits(R, job.kt)) return fail(SPEC_ESHAPE, "internal: closing step on a contraction of %d rows", R);
+  if (fold && !skinny_fits(R, job.kt)) return fail(SPEC_ESHAPE, "internal: folded stage on a contraction of %d rows", R);
+  if (fold) job.fold = *fold;
   if (skinny_fits(R, job.kt)) {
     job.nparts = skinny_grid(m->n_cu);
     *nparts = job.nparts;
     const int slot = prof_slot(m, 0, R, job.n_head + job.n_proj, K);
-    HIP_TRY(launch_head_skinny(job, tail, m->n_cu, st, EV0(slot), EV1(slot)));
+    HIP_TRY(launch_head_skinny(job, m->n_cu, st, EV0(slot), EV1(slot)));
     return SPEC_OK;
   }
   GemmPlan pl = plan_gemm(R, k_top, job.n_head, job.n_proj, job.kt, m->n_cu);
@@ -652,36 +650,7 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, const void
     return tj;
   };
 
-  // Every contraction of the call on the streaming kernel (at most 16 rows per stage: batch 1 with the
-  // paper's trees): no stage or tree launches; each streaming launch closes with the next stage's rows
-  // (the last one with the tree step), computed by its last workgroup.
-  bool tails = m->bf16 && !dyn && ws.tail_counters && skinny_fits(batch, E / 32) && tail_fits(batch, D);
-  for (int i = 0; tails && i < n; ++i) tails = skinny_fits((int)R[i], D / 32) && tail_fits((int)R[i], D);
-  if (tails) {
-    const int grid = skinny_grid(m->n_cu);
-    int nparts = 0;
-    TailJob tj;
-    memset(&tj, 0, sizeof(tj));
-    tj.kind = 1;
-    tj.counters = ws.tail_counters;
-    tj.stage = stage_job(0, 0);
-    spec_status_t s = run_contraction(m, ws, -1, 0, state, true, E, batch, 0, nullptr, ws.pz[0], &nparts, st, nullptr, &tj);
-    if (s != SPEC_OK) return s;
-    for (int i = 0; i < n; ++i) {
-      memset(&tj, 0, sizeof(tj));
-      tj.counters = ws.tail_counters;
-      if (i + 1 < n) {
-        tj.kind = 1;
-        tj.stage = stage_job(i + 1, grid);
-      } else {
-        tj.kind = 2;
-        tj.tree = tree_job(grid);
-      }
-      s = run_contraction(m, ws, i, i + 1 < n ? i + 1 : -1, ws.states, false, D, (int)R[i], top_k[i], nullptr,
-                          ws.pz[(i + 1) & 1], &nparts, st, nullptr, &tj);
-      if (s != SPEC_OK) return s;
-    }
-  } else {
+  {
     int nparts = 1, pz0_parts = 1;
     const bool any_rows = R[0] > 0;   // (per-sequence trees: every sequence may have speculation switched off)
     // projection of the base model's state for stage 1
@@ -700,11 +669,25 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, const void
         sj.pz_parts = pz0_parts;
         sj.pz_part_stride = (int64_t)batch * D;
       }
-      HIP_TRY(launch_stage(sj, st));
+      // First stage of one or two sequences: its rows (token = the last sampled one, no merge) are
+      // computed inside the head's streaming kernel instead of by a launch of their own.
+      FoldJob fold;
+      memset(&fold, 0, sizeof(fold));
+      const bool folded = i == 0 && m->bf16 && !dbg && !dyn && skinny_fits((int)R[0], D / 32) && (int)R[0] <= skinny_fold_rows(D);
+      if (folded) {
+        fold.enabled = 1;
+        fold.D = D; fold.V = V;
+        fold.pz = sj.pz; fold.pz_parts = sj.pz_parts > 0 ? sj.pz_parts : 1; fold.pz_part_stride = sj.pz_part_stride;
+        fold.tok = last_tok;
+        fold.emb = sj.emb; fold.gamma = sj.gamma; fold.beta = sj.beta;
+        fold.w_s = sj.w_s; fold.w_e = sj.w_e; fold.eps = sj.eps;
+      } else {
+        HIP_TRY(launch_stage(sj, st));
+      }
       const int proj_next = i + 1 < n ? i + 1 : -1;
       if (m->bf16) {
         spec_status_t s = run_contraction(m, ws, i, proj_next, ws.states, false, D, (int)R[i], top_k[i], nullptr,
-                                          ws.pz[(i + 1) & 1], &nparts, st);
+                                          ws.pz[(i + 1) & 1], &nparts, st, nullptr, folded ? &fold : nullptr);
         if (s != SPEC_OK) return s;
       } else {
         const float* sf = static_cast<const float*>(ws.states);
@@ -853,9 +836,6 @@ static spec_status_t carve_static(const spec_model* m, unsigned char* base, int 
     if (used > (size_t)SPEC_STATIC_SCRATCH_BYTES) fits = false;
     return p;
   };
-  // (first, at a fixed place: the closing-step counters, zero when the library is loaded and zero again after
-  // every launch that uses them)
-  ws->tail_counters = reinterpret_cast<unsigned*>(take((size_t)kTailCounterWords * 4));
   const int64_t rows16 = (max_rows + 15) / 16 * 16, batch16 = ((int64_t)batch + 15) / 16 * 16;
   const int64_t pz_rows = max_parent > (int64_t)kMaxKSplit * batch ? max_parent : (int64_t)kMaxKSplit * batch;
   // parts per row: one per workgroup of the streaming kernel when every stage has at most 16 rows,

@@ -1,127 +1,19 @@
 // Device-side bodies of the stage step and of the tree step (Sec. 3.1, 4.1 of the
-// paper), shared by the stage / tree kernels and the closing step of the streaming kernel.
+// paper).
 #pragma once
 #include "merge.h"
 #include "spec_internal.h"
 
 namespace specdraft {
 
-// ---- pieces of one stage row, per 8-element chunk c of the row (shared by every kernel that computes
-// stage rows, so that all of them round identically; the compiler may not fuse multiplies and adds on
-// its own here: where a fused multiply-add is wanted it is written out) -----------------------------
-
-// projected parent state: chunk c of row `parent` of j.pz (a projection split along K: parts added in order)
-__device__ __forceinline__ void stage_load_pz(const StageJob& j, int parent, int c, float (&z)[8]) {
-  const float* pz = j.pz + (int64_t)parent * j.D;
-  float4 p0 = *reinterpret_cast<const float4*>(pz + c * 8);
-  float4 p1 = *reinterpret_cast<const float4*>(pz + c * 8 + 4);
-  for (int q = 1; q < j.pz_parts; ++q) {
-    const float* pq = pz + q * j.pz_part_stride + c * 8;
-    const float4 q0 = *reinterpret_cast<const float4*>(pq);
-    const float4 q1 = *reinterpret_cast<const float4*>(pq + 4);
-    p0.x += q0.x; p0.y += q0.y; p0.z += q0.z; p0.w += q0.w;
-    p1.x += q1.x; p1.y += q1.y; p1.z += q1.z; p1.w += q1.w;
-  }
-  z[0] = p0.x; z[1] = p0.y; z[2] = p0.z; z[3] = p0.w;
-  z[4] = p1.x; z[5] = p1.y; z[6] = p1.z; z[7] = p1.w;
-}
-
-__device__ __forceinline__ void stage_load_affine(const StageJob& j, int c, float (&ga)[8], float (&be)[8]) {
-  const float4 g0 = *reinterpret_cast<const float4*>(j.gamma + c * 8);
-  const float4 g1 = *reinterpret_cast<const float4*>(j.gamma + c * 8 + 4);
-  const float4 b0 = *reinterpret_cast<const float4*>(j.beta + c * 8);
-  const float4 b1 = *reinterpret_cast<const float4*>(j.beta + c * 8 + 4);
-  ga[0] = g0.x; ga[1] = g0.y; ga[2] = g0.z; ga[3] = g0.w;
-  ga[4] = g1.x; ga[5] = g1.y; ga[6] = g1.z; ga[7] = g1.w;
-  be[0] = b0.x; be[1] = b0.y; be[2] = b0.z; be[3] = b0.w;
-  be[4] = b1.x; be[5] = b1.y; be[6] = b1.z; be[7] = b1.w;
-}
-
-// embedding chunk of token `tok`
-template <bool BF16>
-__device__ __forceinline__ void stage_load_emb(const StageJob& j, int tok, int c, float (&e)[8]) {
-  if (BF16) {
-    const uint4 raw =
-        *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(j.emb) + (int64_t)tok * j.D + c * 8);
-    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      e[2 * q] = bf16_bits_to_f32(w[q] & 0xffffu);
-      e[2 * q + 1] = bf16_bits_to_f32(w[q] >> 16);
-    }
-  } else {
-    const float* er = static_cast<const float*>(j.emb) + (int64_t)tok * j.D + c * 8;
-    const float4 e0 = *reinterpret_cast<const float4*>(er);
-    const float4 e1 = *reinterpret_cast<const float4*>(er + 4);
-    e[0] = e0.x; e[1] = e0.y; e[2] = e0.z; e[3] = e0.w;
-    e[4] = e1.x; e[5] = e1.y; e[6] = e1.z; e[7] = e1.w;
-  }
-}
-
-// z = w_s * z + w_e * e; returns the chunk's contribution to the row sum
-__device__ __forceinline__ float stage_mix(const StageJob& j, float (&z)[8], const float (&e)[8]) {
-#pragma clang fp contract(off)
-  float lsum = 0.f;
-#pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    z[q] = __builtin_fmaf(j.w_s, z[q], j.w_e * e[q]);
-    lsum += z[q];
-  }
-  return lsum;
-}
-
-__device__ __forceinline__ float stage_sq_dev(const float (&z)[8], float mean) {
-#pragma clang fp contract(off)
-  float lvar = 0.f;
-#pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const float d = z[q] - mean;
-    lvar = __builtin_fmaf(d, d, lvar);
-  }
-  return lvar;
-}
-
-// LayerNorm affine + GELU of chunk c of row r, stored as the stage's state (and the optional debug copy):
-// whole 16-byte slots, the L2 gathers the eight rows that share a 128-byte line.
-template <bool BF16>
-__device__ __forceinline__ void stage_finish(const StageJob& j, int r, int c, const float (&z)[8], float mean,
-                                             float rstd, const float (&ga)[8], const float (&be)[8]) {
-#pragma clang fp contract(off)
-  const int D = j.D;
-  float s[8];
-#pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const float y = __builtin_fmaf((z[q] - mean) * rstd, ga[q], be[q]);
-    s[q] = 0.5f * y * (1.0f + erf_as(y * 0.70710678118654752440f));
-  }
-  if (BF16) {
-    uint4 o;
-    o.x = f32_to_bf16_bits(s[0]) | (f32_to_bf16_bits(s[1]) << 16);
-    o.y = f32_to_bf16_bits(s[2]) | (f32_to_bf16_bits(s[3]) << 16);
-    o.z = f32_to_bf16_bits(s[4]) | (f32_to_bf16_bits(s[5]) << 16);
-    o.w = f32_to_bf16_bits(s[6]) | (f32_to_bf16_bits(s[7]) << 16);
-    // tiled layout: row tile r/16, column fragment c/4, lane slot (c%4)*16 + r%16
-    const int64_t slot = ((int64_t)(r >> 4) * (D / 32) + (c >> 2)) * 64 + ((c & 3) << 4) + (r & 15);
-    reinterpret_cast<uint4*>(j.state_out)[slot] = o;
-    if (j.state_dbg) reinterpret_cast<uint4*>(j.state_dbg)[((int64_t)r * D) / 8 + c] = o;
-  } else {
-    float* so = static_cast<float*>(j.state_out) + (int64_t)r * D + c * 8;
-    *reinterpret_cast<float4*>(so) = make_float4(s[0], s[1], s[2], s[3]);
-    *reinterpret_cast<float4*>(so + 4) = make_float4(s[4], s[5], s[6], s[7]);
-    if (j.state_dbg) {
-      float* sd = static_cast<float*>(j.state_dbg) + (int64_t)r * D + c * 8;
-      *reinterpret_cast<float4*>(sd) = make_float4(s[0], s[1], s[2], s[3]);
-      *reinterpret_cast<float4*>(sd + 4) = make_float4(s[4], s[5], s[6], s[7]);
-    }
-  }
-}
-
 // One node (child row r) of a stage, computed by a whole workgroup of NT threads:
 //   state = GELU(LayerNorm(w_s * (W s_parent) + w_e * Emb[token]))
 // The token the node carries is the rank-th best of its parent's head row; that row's
-// partial results are merged here (every sibling repeats the small merge).
+// partial results are merged here (every sibling repeats the small merge, which saves
+// a separate launch on the latency-critical batch-1 chain).
 // NCH = 8-element chunks per thread held in registers (D <= NCH * NT * 8).
 // `lds`: (NT / 256) * 32 + 32 words of scratch.  Contains workgroup barriers.
+// States are stored as whole 16-byte slots; the L2 gathers the eight rows that share a 128-byte line.
 template <bool BF16, int NCH, int NT>
 __device__ __forceinline__ void stage_row(const StageJob& j, int r, float* lds) {
   float* scratch = lds;                 // NT / 64 <= 16 words
@@ -136,13 +28,31 @@ __device__ __forceinline__ void stage_row(const StageJob& j, int r, float* lds) 
 
   // everything that does not depend on the token is requested first: the
   // projected parent state and the LayerNorm affine
+  const float* pz = j.pz + (int64_t)parent * D;
   float z[NCH][8], ga[NCH][8], be[NCH][8];
 #pragma unroll
   for (int ci = 0; ci < NCH; ++ci) {
     const int c = tid + ci * NT;
     if (c < nchunk) {
-      stage_load_pz(j, parent, c, z[ci]);
-      stage_load_affine(j, c, ga[ci], be[ci]);
+      float4 p0 = *reinterpret_cast<const float4*>(pz + c * 8);
+      float4 p1 = *reinterpret_cast<const float4*>(pz + c * 8 + 4);
+      for (int q = 1; q < j.pz_parts; ++q) {  // a projection split along K: add the parts in order
+        const float* pq = pz + q * j.pz_part_stride + c * 8;
+        const float4 q0 = *reinterpret_cast<const float4*>(pq);
+        const float4 q1 = *reinterpret_cast<const float4*>(pq + 4);
+        p0.x += q0.x; p0.y += q0.y; p0.z += q0.z; p0.w += q0.w;
+        p1.x += q1.x; p1.y += q1.y; p1.z += q1.z; p1.w += q1.w;
+      }
+      const float4 g0 = *reinterpret_cast<const float4*>(j.gamma + c * 8);
+      const float4 g1 = *reinterpret_cast<const float4*>(j.gamma + c * 8 + 4);
+      const float4 b0 = *reinterpret_cast<const float4*>(j.beta + c * 8);
+      const float4 b1 = *reinterpret_cast<const float4*>(j.beta + c * 8 + 4);
+      z[ci][0] = p0.x; z[ci][1] = p0.y; z[ci][2] = p0.z; z[ci][3] = p0.w;
+      z[ci][4] = p1.x; z[ci][5] = p1.y; z[ci][6] = p1.z; z[ci][7] = p1.w;
+      ga[ci][0] = g0.x; ga[ci][1] = g0.y; ga[ci][2] = g0.z; ga[ci][3] = g0.w;
+      ga[ci][4] = g1.x; ga[ci][5] = g1.y; ga[ci][6] = g1.z; ga[ci][7] = g1.w;
+      be[ci][0] = b0.x; be[ci][1] = b0.y; be[ci][2] = b0.z; be[ci][3] = b0.w;
+      be[ci][4] = b1.x; be[ci][5] = b1.y; be[ci][6] = b1.z; be[ci][7] = b1.w;
     }
   }
 
@@ -179,153 +89,81 @@ __device__ __forceinline__ void stage_row(const StageJob& j, int r, float* lds) 
     const int c = tid + ci * NT;
     if (c < nchunk) {
       float e[8];
-      stage_load_emb<BF16>(j, tok, c, e);
-      lsum += stage_mix(j, z[ci], e);
+      if (BF16) {
+        const uint4 raw =
+            *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(j.emb) + (int64_t)tok * D + c * 8);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          e[2 * q] = bf16_bits_to_f32(w[q] & 0xffffu);
+          e[2 * q + 1] = bf16_bits_to_f32(w[q] >> 16);
+        }
+      } else {
+        const float* er = static_cast<const float*>(j.emb) + (int64_t)tok * D + c * 8;
+        const float4 e0 = *reinterpret_cast<const float4*>(er);
+        const float4 e1 = *reinterpret_cast<const float4*>(er + 4);
+        e[0] = e0.x; e[1] = e0.y; e[2] = e0.z; e[3] = e0.w;
+        e[4] = e1.x; e[5] = e1.y; e[6] = e1.z; e[7] = e1.w;
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        z[ci][q] = j.w_s * z[ci][q] + j.w_e * e[q];
+        lsum += z[ci][q];
+      }
     }
   }
   const float mean = block_sum<NT>(lsum, scratch) / (float)D;
   float lvar = 0.f;
 #pragma unroll
-  for (int ci = 0; ci < NCH; ++ci)
-    if (tid + ci * NT < nchunk) lvar += stage_sq_dev(z[ci], mean);
+  for (int ci = 0; ci < NCH; ++ci) {
+    if (tid + ci * NT < nchunk) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const float d = z[ci][q] - mean;
+        lvar += d * d;
+      }
+    }
+  }
   const float var = block_sum<NT>(lvar, scratch) / (float)D;
   const float rstd = 1.0f / sqrtf(var + j.eps);
 
 #pragma unroll
   for (int ci = 0; ci < NCH; ++ci) {
     const int c = tid + ci * NT;
-    if (c < nchunk) stage_finish<BF16>(j, r, c, z[ci], mean, rstd, ga[ci], be[ci]);
-  }
-}
-
-// All rows of a stage by ONE workgroup of 1024 threads (a stage of at most 16 rows: the batch-1 regime),
-// as the closing step of the launch that produced the previous head's partial results: the partials are
-// merged (tables of the previous stage), then the rows are computed four at a time, one per 256-thread
-// group, with exactly stage_row's arithmetic at 256 threads; two such rounds share their memory round
-// trips.  NCH = chunks per thread (D <= NCH * 2048).
-// `lds`: 32 + 64 + 128 words.  Contains workgroup barriers; uniform tree only (no row maps).
-template <int NCH>
-__device__ __forceinline__ void stage_all_rows(const StageJob& sj, float* lds) {
-  constexpr int RP = 2;  // rounds per pass
-  int32_t* s_tok = reinterpret_cast<int32_t*>(lds);   // [16] token of every row of the stage
-  float* red = lds + 32;                              // [2][RP][16] wave sums
-  float* merge_lds = lds + 32 + 2 * RP * 16;          // [4][32]
-  const int tid = opaque_tid(), lane = tid & 63, wave = tid >> 6, grp = tid >> 8, gt = tid & 255;
-  const int R = sj.R, D = sj.D, nchunk = D / 8, k = sj.k_prev;
-
-  // ---- tokens of the rows
-  if (sj.stage == 0) {
-    if (tid < R) s_tok[tid] = sj.last_tok[tid];
-  } else {
-    const int P = R / k;   // parent rows
-    if (k <= 4) {
-      if (wave < P) {
-        float v[kMaxTopK];
-        int32_t ix[kMaxTopK];
-        float lse;
-        wave_merge_partials_k<4>(sj.part, wave, sj.nparts, k, v, ix, lse);
+    if (c < nchunk) {
+      float s[8];
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-          if (lane == t && t < k) {
-            sj.prev_tok[(int64_t)wave * k + t] = ix[t];
-            sj.prev_logp[(int64_t)wave * k + t] = v[t] - lse;
-            s_tok[wave * k + t] = ix[t];
-          }
-        if (lane == 0) sj.prev_lse[wave] = lse;
+      for (int q = 0; q < 8; ++q) {
+        const float y = (z[ci][q] - mean) * rstd * ga[ci][q] + be[ci][q];
+        s[q] = 0.5f * y * (1.0f + erf_as(y * 0.70710678118654752440f));
       }
-    } else {
-      for (int p0 = 0; p0 < P; p0 += 4) {
-        const bool live = p0 + grp < P;
-        const int row = live ? p0 + grp : P - 1;
-        float v[kMaxTopK];
-        int32_t ix[kMaxTopK];
-        float lse;
-        group_merge_partials(sj.part, row, sj.nparts, k, v, ix, lse, merge_lds + grp * 32);
-#pragma unroll
-        for (int t = 0; t < kMaxTopK; ++t)
-          if (live && gt == t && t < k) {
-            sj.prev_tok[(int64_t)row * k + t] = ix[t];
-            sj.prev_logp[(int64_t)row * k + t] = v[t] - lse;
-            s_tok[row * k + t] = ix[t];
-          }
-        if (live && gt == 0) sj.prev_lse[row] = lse;
-      }
-    }
-  }
-  __syncthreads();
-
-  // ---- the rows
-  float ga[NCH][8], be[NCH][8];
-#pragma unroll
-  for (int ci = 0; ci < NCH; ++ci) {
-    const int c = gt + ci * 256;
-    if (c < nchunk) stage_load_affine(sj, c, ga[ci], be[ci]);
-  }
-  for (int r0 = 0; r0 < R; r0 += 4 * RP) {
-    float z[RP][NCH][8], lsum[RP];
-    // every load of the pass is issued before the first use
-#pragma unroll
-    for (int rr = 0; rr < RP; ++rr) {
-      const int r = r0 + rr * 4 + grp;
-      lsum[rr] = 0.f;
-      if (r < R) {
-        const int tok = min(max(s_tok[r], 0), sj.V - 1);
-        float e[NCH][8];
-#pragma unroll
-        for (int ci = 0; ci < NCH; ++ci) {
-          const int c = gt + ci * 256;
-          if (c < nchunk) {
-            stage_load_pz(sj, r / k, c, z[rr][ci]);
-            stage_load_emb<true>(sj, tok, c, e[ci]);
-          }
-        }
-#pragma unroll
-        for (int ci = 0; ci < NCH; ++ci)
-          if (gt + ci * 256 < nchunk) lsum[rr] += stage_mix(sj, z[rr][ci], e[ci]);
-      }
-    }
-    // row sums over the group's four waves, added in wave order (as block_sum<256> does)
-#pragma unroll
-    for (int rr = 0; rr < RP; ++rr) {
-      const float s = wave_sum(lsum[rr]);
-      if (lane == 0) red[rr * 16 + wave] = s;
-    }
-    __syncthreads();
-    float mean[RP];
-#pragma unroll
-    for (int rr = 0; rr < RP; ++rr) {
-      float t = 0.f;
-      for (int q = 0; q < 4; ++q) t += red[rr * 16 + grp * 4 + q];
-      mean[rr] = t / (float)D;
-      float lvar = 0.f;
-      if (r0 + rr * 4 + grp < R) {
-#pragma unroll
-        for (int ci = 0; ci < NCH; ++ci)
-          if (gt + ci * 256 < nchunk) lvar += stage_sq_dev(z[rr][ci], mean[rr]);
-      }
-      const float s = wave_sum(lvar);
-      if (lane == 0) red[(RP + rr) * 16 + wave] = s;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int rr = 0; rr < RP; ++rr) {
-      float t = 0.f;
-      for (int q = 0; q < 4; ++q) t += red[(RP + rr) * 16 + grp * 4 + q];
-      const float var = t / (float)D;
-      const float rstd = 1.0f / sqrtf(var + sj.eps);
-      const int r = r0 + rr * 4 + grp;
-      if (r < R) {
-#pragma unroll
-        for (int ci = 0; ci < NCH; ++ci) {
-          const int c = gt + ci * 256;
-          if (c < nchunk) stage_finish<true>(sj, r, c, z[rr][ci], mean[rr], rstd, ga[ci], be[ci]);
+      if (BF16) {
+        uint4 o;
+        o.x = f32_to_bf16_bits(s[0]) | (f32_to_bf16_bits(s[1]) << 16);
+        o.y = f32_to_bf16_bits(s[2]) | (f32_to_bf16_bits(s[3]) << 16);
+        o.z = f32_to_bf16_bits(s[4]) | (f32_to_bf16_bits(s[5]) << 16);
+        o.w = f32_to_bf16_bits(s[6]) | (f32_to_bf16_bits(s[7]) << 16);
+        // tiled layout: row tile r/16, column fragment c/4, lane slot (c%4)*16 + r%16
+        const int64_t slot = ((int64_t)(r >> 4) * (D / 32) + (c >> 2)) * 64 + ((c & 3) << 4) + (r & 15);
+        reinterpret_cast<uint4*>(j.state_out)[slot] = o;
+        if (j.state_dbg) reinterpret_cast<uint4*>(j.state_dbg)[((int64_t)r * D) / 8 + c] = o;
+      } else {
+        float* so = static_cast<float*>(j.state_out) + (int64_t)r * D + c * 8;
+        *reinterpret_cast<float4*>(so) = make_float4(s[0], s[1], s[2], s[3]);
+        *reinterpret_cast<float4*>(so + 4) = make_float4(s[4], s[5], s[6], s[7]);
+        if (j.state_dbg) {
+          float* sd = static_cast<float*>(j.state_dbg) + (int64_t)r * D + c * 8;
+          *reinterpret_cast<float4*>(sd) = make_float4(s[0], s[1], s[2], s[3]);
+          *reinterpret_cast<float4*>(sd + 4) = make_float4(s[4], s[5], s[6], s[7]);
         }
       }
     }
-    __syncthreads();   // `red` is written again by the next pass
   }
 }
 
+// Tree step for one sequence q, by a whole workgroup of NT threads: merge the last
+// head's partial results, score every leaf by the sum of its tokens' log-probabilities
+// (added in stage order), keep the B best.
 struct TreeArgs {
   int n, B, B_pad, L, k_last, kw_last, nparts;
   int64_t off_last, row_off_last;   // the last stage's offsets in tok / logp and in lse

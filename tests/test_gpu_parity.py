@@ -95,31 +95,31 @@ def test_small_bf16_shapes(case):
     assert rep.rows_exempt <= 1
 
 
-# Every stage at most 16 rows: the streaming kernel with its closing step (the launch's last workgroup
-# computes the next stage's rows / the tree step) - widths that take one and two chunks per thread there,
-# every merge width, several sequences, a 7-stage chain.
-CLOSING_STEP_BF16 = [
-    ("tail_d512_rows_1_5_15", 512, 512, 1000, 3, (5, 3, 2), 10, 1),    # the paper's tree shape, ragged vocabulary
-    ("tail_d1024_b2", 1024, 1024, 2049, 3, (2, 2, 2), 8, 2),           # two sequences: 2, 4, 8 rows
-    ("tail_d2048_k8", 2048, 2048, 777, 2, (8, 8), 64, 2),              # 16 rows, widest top-k: group merges
-    ("tail_d512_chain_n7", 512, 512, 500, 7, (1,) * 7, 1, 2),          # k = 1 chain
-    ("tail_d3072_b1", 3072, 3072, 640, 2, (6, 2), 12, 1),              # two chunks per thread, merge width 6
-    ("tail_d1536_b1", 512, 1536, 700, 2, (8, 2), 16, 1),               # E != D, 192 chunks per row
-    ("tail_d4096_b2_chain", 512, 4096, 300, 4, (1,) * 4, 1, 2),        # the 7B width
-    ("tail_d512_b3", 512, 512, 1000, 3, (3, 2, 1), 6, 3),              # 3, 9, 18 rows: 18 > 16, the last stage leaves the path
-    ("tail_d4096_rows_16", 4096, 4096, 300, 3, (4, 4, 1), 16, 1),      # 16 rows: four rounds in two passes
-    ("tail_d256_b16", 128, 256, 500, 2, (1, 1), 1, 16),                # 16 sequences: the tree step loops over them
+# Every stage at most 16 rows: the streaming kernel for every contraction - widths with one and two chunks
+# per thread in the stage kernel, every merge width, several sequences, a 7-stage chain; with one or two
+# sequences and no debug outputs the first stage is computed inside the first head's launch.
+STREAMING_BF16 = [
+    ("stream_d512_rows_1_5_15", 512, 512, 1000, 3, (5, 3, 2), 10, 1),    # the paper's tree shape, ragged vocabulary
+    ("stream_d1024_b2", 1024, 1024, 2049, 3, (2, 2, 2), 8, 2),           # two sequences: 2, 4, 8 rows
+    ("stream_d2048_k8", 2048, 2048, 777, 2, (8, 8), 64, 2),              # 16 rows, widest top-k: group merges
+    ("stream_d512_chain_n7", 512, 512, 500, 7, (1,) * 7, 1, 2),          # k = 1 chain
+    ("stream_d3072_b1", 3072, 3072, 640, 2, (6, 2), 12, 1),              # two chunks per thread, merge width 6
+    ("stream_d1536_b1", 512, 1536, 700, 2, (8, 2), 16, 1),               # E != D, 192 chunks per row
+    ("stream_d4096_b2_chain", 512, 4096, 300, 4, (1,) * 4, 1, 2),        # the 7B width
+    ("stream_d512_b3", 512, 512, 1000, 3, (3, 2, 1), 6, 3),              # 3, 9, 18 rows: the last stage takes the dense kernel
+    ("stream_d4096_rows_16", 4096, 4096, 300, 3, (4, 4, 1), 16, 1),      # 16 rows: four rounds in two passes
+    ("stream_d256_b16", 128, 256, 500, 2, (1, 1), 1, 16),                # 16 sequences: the tree step loops over them
 ]
 
 
-@pytest.mark.parametrize("case", CLOSING_STEP_BF16, ids=[c[0] for c in CLOSING_STEP_BF16])
-def test_streaming_launches_with_closing_step(case):
+@pytest.mark.parametrize("case", STREAMING_BF16, ids=[c[0] for c in STREAMING_BF16])
+def test_streaming_kernel_shapes(case):
     name, E, D, V, n, top_k, Bc, batch = case
     wl = W.Workload(name, E, D, V, n, top_k, Bc, batch, "bf16", "f32", 0.6, seed=17, emb_std=0.3)
     rep, step, od, ov = run_workload(wl, ln_affine="random", gen_device="cpu")
     assert rep.rows_checked + rep.rows_skipped_below_exempt == sum(wl.rows())
     assert rep.rows_exempt <= 1
-    # repeated calls on the same model (the closing step's counters return to zero by themselves)
+    # repeated calls on the same model
     gen = W.make_generator(wl.seed, "cpu")
     W.make_speculator(wl, gen, device="cpu", ln_affine="random")
     state, last = W.make_draft_inputs(wl, gen, device="cpu")
