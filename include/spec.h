@@ -293,9 +293,12 @@ typedef struct {
   int32_t ranges;       /* workgroups per row block; each owns a contiguous range of the tiles */
   int32_t tiles;        /* tiles of both weight matrices together */
   int32_t parts;        /* partial (log-sum-exp, top-k) results per row handed to the merge */
-  int32_t k_split;      /* workgroups per tile along k (projection alone), 1 otherwise */
+  int32_t k_split;      /* workgroups per tile along k (a projection alone), 1 otherwise */
   int32_t workgroups;   /* row_blocks * ranges * k_split */
   int32_t lds_bytes;    /* dynamic LDS per workgroup */
+  int32_t proj_apart;   /* 1: spec_draft does not launch this pair as one contraction (its tile list would make
+                           the launch one tile longer for a few ranges) but as two, whose plans are those of
+                           (n_head, 0) and (0, n_proj); the other fields describe the single launch anyway */
 } spec_plan_t;
 /* SPEC_EINVAL: arguments out of range; SPEC_ESHAPE: no kernel instance serves the plan (a library bug). */
 spec_status_t spec_plan_contraction(int32_t rows, int32_t k, int32_t n_head, int32_t k_top, int32_t n_proj,

@@ -44,7 +44,7 @@ class spec_weights_t(C.Structure):
 
 class spec_plan_t(C.Structure):
     _fields_ = [(name, C.c_int32) for name in ("kernel", "block_rows", "tile_rows", "row_blocks", "ranges", "tiles",
-                                               "parts", "k_split", "workgroups", "lds_bytes")]
+                                               "parts", "k_split", "workgroups", "lds_bytes", "proj_apart")]
 
 
 class spec_debug_t(C.Structure):

@@ -133,7 +133,14 @@ GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
         if (cost < best) { best = cost; pl = alt; }
       }
     }
-    shrink_tile(pl, R, n_head, n_proj, n_cu);
+    // a projection alone: a few dozen workgroups; K is split over more (all four waves stay busy, which
+    // short tiles would not give; the consumer adds the parts)
+    if (n_head == 0) {
+      const int cus = n_cu > 0 ? n_cu : 256;
+      while (pl.ksplit < kMaxKSplit && pl.m_tiles * pl.n_ranges * pl.ksplit * 2 <= cus && kt / KS / (pl.ksplit * 2) >= 8)
+        pl.ksplit *= 2;
+    }
+    if (pl.ksplit == 1) shrink_tile(pl, R, n_head, n_proj, n_cu);
     return pl;
   }
   fill_plan(pl, R, n_head, n_proj, n_cu);
@@ -147,6 +154,27 @@ GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
       pl.ksplit *= 2;
   }
   return pl;
+}
+
+// Cost of a launch in units of one 96-row-block tile: the longest range decides.
+static double plan_cost(const GemmPlan& pl, int n_head, int n_proj) {
+  const int total = plan_tiles(n_head, pl.ts) + plan_tiles(n_proj, pl.ts);
+  const double per_tile = pl.mi >= 10 ? kTallSlabCost : (pl.mi >= 8 ? kMidSlabCost : 1.0);
+  return per_tile * ((total + pl.n_ranges - 1) / pl.n_ranges) / pl.ksplit;
+}
+
+// Head and next projection in ONE launch share the state reads, but their tiles form one list, and a list
+// that is a little longer than a multiple of the ranges makes the launch one tile longer for a few ranges
+// (320 rows against 125 + 16 tiles: 128 ranges, 13 of them with two tiles).  Then two launches are cheaper:
+// the head alone in one even round, the projection alone split along K over the whole chip.
+bool plan_projection_apart(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
+  if (R <= 64 || n_head <= 0 || n_proj <= 0) return false;   // wide kernel only
+  const GemmPlan both = plan_gemm(R, k_top, n_head, n_proj, kt, n_cu);
+  const GemmPlan head = plan_gemm(R, k_top, n_head, 0, kt, n_cu);
+  const GemmPlan proj = plan_gemm(R, 0, 0, n_proj, kt, n_cu);
+  if (both.ni != 4 || head.ni != 4 || proj.ni != 4) return false;
+  const double launch = 0.15;   // a second launch: drain, start, pipeline fill, partial sums read back
+  return plan_cost(head, n_head, 0) + plan_cost(proj, 0, n_proj) + launch < plan_cost(both, n_head, n_proj) - 0.05;
 }
 
 struct GemmArgs {
@@ -163,7 +191,7 @@ struct GemmArgs {
   int R, mt_total;
   int m_tiles, n_ranges, chunk;  // chunk = workgroups per XCD
   int ts;                        // 16-row weight tiles per workgroup tile (wide kernel)
-  int ksplit;                    // narrow kernel, store epilogue: workgroups per tile along K
+  int ksplit;                    // a projection alone (store epilogue): workgroups per tile along K
   int64_t out_part_stride;       // floats between the K parts' outputs
   int k_top;
   Partials part;
@@ -526,14 +554,17 @@ __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
   const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
   if (seq >= p.chunk) return;
   const int wg = xcd * p.chunk + seq;
-  if (wg >= p.m_tiles * p.n_ranges) return;
-  const int range = wg / p.m_tiles, mtile = wg - range * p.m_tiles;
+  if (wg >= p.m_tiles * p.n_ranges * p.ksplit) return;
+  // K split (a projection alone, store epilogue): part kpart of a tile covers slabs [slab0, slab0 + nslab)
+  const int kpart = wg % p.ksplit, wg2 = wg / p.ksplit;
+  const int range = wg2 / p.m_tiles, mtile = wg2 - range * p.m_tiles;
   const int total_tiles = p.n_tiles[0] + p.n_tiles[1];
   const int t0 = (int)((int64_t)range * total_tiles / p.n_ranges);
   const int t1 = (int)((int64_t)(range + 1) * total_tiles / p.n_ranges);
 
   const int kt = p.kt;
-  const int nslab = kt / KS;
+  const int slab0 = (int)((int64_t)kpart * (kt / KS) / p.ksplit);
+  const int nslab = (int)((int64_t)(kpart + 1) * (kt / KS) / p.ksplit) - slab0;
   // staging sources of this thread (the same for every tile of the range)
   const u32x4* sptr[SPT];
 #pragma unroll
@@ -541,7 +572,7 @@ __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
     const int i = s * 256 + tid;
     const int mtl = i / (KS * 64), rem = i % (KS * 64);
     const int mt = min(mtile * MI + mtl, p.mt_total - 1);
-    sptr[s] = p.b + (int64_t)mt * kt * 64 + rem;
+    sptr[s] = p.b + (int64_t)mt * kt * 64 + (int64_t)slab0 * KS * 64 + rem;
   }
 
   // weight fragment pointers of this wave for a given tile of the list
@@ -560,7 +591,7 @@ __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
     for (int nb = 0; nb < NB; ++nb) {
       ntv[nb] = ntile * ts + wave * NI + 2 * nb;  // first 16-row tile of the block
       const int ntc = min(ntv[nb] + (c32 >> 4), tend - 1);
-      wp[nb] = p.w[mat] + (int64_t)ntc * kt * 64 + half * 16 + (c32 & 15);
+      wp[nb] = p.w[mat] + (int64_t)ntc * kt * 64 + (int64_t)slab0 * KS * 64 + half * 16 + (c32 & 15);
     }
   };
 
@@ -724,7 +755,7 @@ __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int v0 = cur_nt[nb] * 16 + half * 4 + 8 * q;
-            float* o = p.out[cur_mat] + (int64_t)r * p.ldo[cur_mat] + v0;
+            float* o = p.out[cur_mat] + kpart * p.out_part_stride + (int64_t)r * p.ldo[cur_mat] + v0;
             if (v0 + 3 < n_valid && (p.ldo[cur_mat] & 3) == 0) {
               *reinterpret_cast<float4*>(o) = make_float4(acc[mb][nb][4 * q], acc[mb][nb][4 * q + 1],
                                                           acc[mb][nb][4 * q + 2], acc[mb][nb][4 * q + 3]);
@@ -930,8 +961,8 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
   a.ts = pl.ts;
   a.ksplit = 1;
   if (pl.ksplit > 1) {
-    // only a projection alone, on the narrow kernel, with room for the parts
-    if (pl.ni != 1 || job.vt_head > 0 || job.proj_part_stride <= 0 || (job.proj_part_stride & 3)) return hipErrorInvalidValue;
+    // only a projection alone, with room for the parts
+    if (job.vt_head > 0 || job.proj_part_stride <= 0 || (job.proj_part_stride & 3)) return hipErrorInvalidValue;
     a.ksplit = pl.ksplit;
     a.out_part_stride = job.proj_part_stride;
   }

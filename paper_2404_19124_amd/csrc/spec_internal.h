@@ -113,10 +113,12 @@ struct GemmPlan {
   int m_tiles;       // blocks of state rows
   int n_ranges;      // ranges of weight-row tiles
   int nparts;        // ranges that hold head tiles = parts per row
-  int ksplit;        // parts of K (> 1 only for a projection alone on the narrow kernel)
+  int ksplit;        // parts of K (> 1 only for a projection alone)
 };
 constexpr int kMaxKSplit = 4;
 GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu);
+// true: the head and the next projection are cheaper as two launches than as one
+bool plan_projection_apart(int R, int k_top, int n_head, int n_proj, int kt, int n_cu);
 // dry != nullptr: nothing is launched (no HIP call at all); the result says whether a kernel
 // instance exists for the plan, and *dry receives its LDS bytes.
 hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& plan, hipStream_t st, hipEvent_t ev_start = nullptr,

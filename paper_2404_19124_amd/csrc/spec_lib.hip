@@ -311,8 +311,8 @@ extern "C" spec_status_t spec_create(const spec_config_t* cfg, const spec_weight
   TRY_FREE(dev_alloc(m, &m->ws.state_in, m->bf16 ? (size_t)batch16 * E * 2 : 16));
   HIP_TRY_FREE(hipMemsetAsync(m->ws.states, 0, (size_t)rows16 * D * m->esz, stream));
   if (m->bf16) HIP_TRY_FREE(hipMemsetAsync(m->ws.state_in, 0, (size_t)batch16 * E * 2, stream));
-  // (the first projection may come as kMaxKSplit partial sums of max_batch rows each)
-  const int64_t pz_rows = max_parent > (int64_t)kMaxKSplit * cfg->max_batch ? max_parent : (int64_t)kMaxKSplit * cfg->max_batch;
+  // (a projection launched on its own may come as kMaxKSplit partial sums)
+  const int64_t pz_rows = (int64_t)kMaxKSplit * max_parent;
   for (int q = 0; q < 2; ++q) TRY_FREE(dev_alloc(m, &m->ws.pz[q], (size_t)pz_rows * D * 4));
   m->ws.part_rows_parts = partial_capacity(max_rows, V, m->n_cu);
   TRY_FREE(dev_alloc(m, &m->ws.part.m, (size_t)m->ws.part_rows_parts * 4));
@@ -449,6 +449,7 @@ extern "C" spec_status_t spec_plan_contraction(int32_t rows, int32_t k, int32_t 
   out->k_split = pl.ksplit;
   out->workgroups = pl.m_tiles * pl.n_ranges * pl.ksplit;
   out->lds_bytes = (int32_t)lds;
+  out->proj_apart = plan_projection_apart(rows, job.k_top, n_head, n_proj, kt, n_cu) ? 1 : 0;
   return SPEC_OK;
 }
 
@@ -663,12 +664,13 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, const void
                               D, batch, D, E, st));
     }
 
+    int pz_parts = pz0_parts;                 // parts of the projection the current stage reads
+    int64_t pz_part_stride = (int64_t)batch * D;
     for (int i = 0; any_rows && i < n; ++i) {
       StageJob sj = stage_job(i, nparts);
-      if (i == 0) {
-        sj.pz_parts = pz0_parts;
-        sj.pz_part_stride = (int64_t)batch * D;
-      }
+      sj.pz_parts = pz_parts;
+      sj.pz_part_stride = pz_part_stride;
+      pz_parts = 1;
       // First stage of one or two sequences: its rows (token = the last sampled one, no merge) are
       // computed inside the head's streaming kernel instead of by a launch of their own.
       FoldJob fold;
@@ -685,7 +687,18 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, const void
         HIP_TRY(launch_stage(sj, st));
       }
       const int proj_next = i + 1 < n ? i + 1 : -1;
-      if (m->bf16) {
+      if (m->bf16 && proj_next >= 0 && !skinny_fits((int)R[i], D / 32) &&
+          plan_projection_apart((int)R[i], top_k[i], V, D, D / 32, m->n_cu)) {
+        // the head in one even round of tiles, then the next projection on its own, split along K
+        spec_status_t s = run_contraction(m, ws, i, -1, ws.states, false, D, (int)R[i], top_k[i], nullptr, nullptr,
+                                          &nparts, st);
+        if (s != SPEC_OK) return s;
+        int np_unused = 0;
+        s = run_contraction(m, ws, -1, proj_next, ws.states, false, D, (int)R[i], 0, nullptr, ws.pz[(i + 1) & 1],
+                            &np_unused, st, &pz_parts);
+        if (s != SPEC_OK) return s;
+        pz_part_stride = R[i] * D;
+      } else if (m->bf16) {
         spec_status_t s = run_contraction(m, ws, i, proj_next, ws.states, false, D, (int)R[i], top_k[i], nullptr,
                                           ws.pz[(i + 1) & 1], &nparts, st, nullptr, folded ? &fold : nullptr);
         if (s != SPEC_OK) return s;
@@ -837,7 +850,7 @@ static spec_status_t carve_static(const spec_model* m, unsigned char* base, int 
     return p;
   };
   const int64_t rows16 = (max_rows + 15) / 16 * 16, batch16 = ((int64_t)batch + 15) / 16 * 16;
-  const int64_t pz_rows = max_parent > (int64_t)kMaxKSplit * batch ? max_parent : (int64_t)kMaxKSplit * batch;
+  const int64_t pz_rows = (int64_t)kMaxKSplit * max_parent;
   // parts per row: one per workgroup of the streaming kernel when every stage has at most 16 rows,
   // else what the dense plans may produce
   const int64_t cap = max_rows <= 16 && m->bf16 ? 16 * (int64_t)skinny_grid(m->n_cu) : partial_capacity(max_rows, V, m->n_cu);

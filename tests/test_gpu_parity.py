@@ -78,6 +78,11 @@ SMALL_BF16 = [
     # first projection split along K (long E, more than 16 rows): four parts, and two parts with two row blocks
     ("bf16_b20_long_e", 2048, 64, 300, 2, (2, 2), 4, 20),
     ("bf16_b40_long_e", 1024, 128, 300, 2, (3, 2), 6, 40),
+    # a first projection of more than 64 rows: the wide kernel's store epilogue with four K parts
+    ("bf16_b70_long_e", 2048, 64, 300, 2, (2, 2), 4, 70),
+    # head and next projection launched apart (254 + 4 tiles against 256 ranges would make two ranges two tiles
+    # long): the head alone, then the projection with two K parts on the wide kernel (155 rows)
+    ("bf16_b31_proj_apart", 128, 1024, 65000, 3, (5, 2, 2), 6, 31),
     # the limits of the boundary: 4096 leaves with top-k 8 everywhere (rows 1, 8, 64, 512), eight stages,
     # a vocabulary smaller than one 16-row tile
     ("bf16_max_leaves", 64, 64, 300, 4, (8, 8, 8, 8), 64, 1),
@@ -90,9 +95,15 @@ SMALL_BF16 = [
 def test_small_bf16_shapes(case):
     name, E, D, V, n, top_k, Bc, batch = case
     wl = W.Workload(name, E, D, V, n, top_k, Bc, batch, "bf16", "f32", 0.6, seed=11, emb_std=0.3)
+    if name == "bf16_b31_proj_apart":   # the case does take the path it is meant for
+        assert B.spec_plan_contraction(155, D, V, 2, D)["proj_apart"] == 1
+        assert B.spec_plan_contraction(155, D, 0, 0, D)["k_split"] == 2
+    if name == "bf16_b70_long_e":
+        p = B.spec_plan_contraction(70, E, 0, 0, D)
+        assert p["kernel"] >= 1000 and p["k_split"] == 4
     rep, step, od, ov = run_workload(wl, ln_affine="random", gen_device="cpu")
     assert rep.rows_checked + rep.rows_skipped_below_exempt == sum(wl.rows())
-    assert rep.rows_exempt <= 1
+    assert rep.rows_exempt <= max(1, sum(wl.rows()) // 100)
 
 
 # Every stage at most 16 rows: the streaming kernel for every contraction - widths with one and two chunks

@@ -35,8 +35,17 @@ def check_plan(rows, k, n_head, k_top, n_proj, n_cu):
     assert 0 < p["lds_bytes"] <= LDS_PER_CU, what
     narrow = p["kernel"] in (1, 2)
     if p["k_split"] > 1:
-        assert narrow and n_head == 0, what
-        assert (k // 64) // p["k_split"] >= 8 and p["workgroups"] <= 2 * n_cu, what
+        assert p["kernel"] != 0 and n_head == 0, what
+        assert (k // 64) // p["k_split"] >= 8 and p["workgroups"] <= (2 if narrow else 1) * n_cu, what
+    if p["proj_apart"]:
+        # two launches instead of one: both halves have plans of their own, on the wide kernel
+        assert rows > 64 and n_head > 0 and n_proj > 0 and p["kernel"] >= 1000, what
+        head = B.spec_plan_contraction(rows, k, n_head, k_top, 0, n_cu)
+        proj = B.spec_plan_contraction(rows, k, 0, 0, n_proj, n_cu)
+        assert head["kernel"] >= 1000 and proj["kernel"] >= 1000, what
+        # the head alone needs fewer tile rounds than the pair
+        per = lambda q: -(-q["tiles"] // q["ranges"])
+        assert per(head) < per(p) or head["block_rows"] != p["block_rows"], what
     if p["kernel"] >= 1000:   # wide kernel: one workgroup per CU unless there are more row blocks than CUs
         assert p["workgroups"] <= max(n_cu, p["row_blocks"]), what
         assert p["tile_rows"] <= 256 and p["block_rows"] in (64, 96, 128, 160), what
@@ -78,7 +87,9 @@ PINNED = [
     ((15, 4096, 32000, 2, 0), (0, 16, 16, 1, 256, 256, 1)),
     ((64, 4096, 0, 0, 4096), (1, 32, 64, 2, 64, 0, 4)),
     ((64, 4096, 32000, 5, 4096), (1217, 64, 144, 1, 252, 223, 1)),
-    ((320, 4096, 32000, 3, 4096), (1408, 128, 256, 3, 85, 76, 1)),
+    ((320, 4096, 32000, 3, 4096), (1408, 128, 256, 3, 85, 76, 1)),     # not launched like this: proj_apart
+    ((320, 4096, 32000, 3, 0), (1508, 160, 256, 2, 125, 125, 1)),      # the head alone: one tile per range
+    ((320, 4096, 0, 0, 4096), (1304, 96, 256, 4, 16, 0, 4)),           # the projection alone, four K parts
     ((960, 4096, 32000, 2, 0), (1504, 160, 256, 6, 42, 42, 1)),
     ((384, 4096, 32000, 3, 0), (1308, 96, 256, 4, 64, 64, 1)),
     ((2304, 3072, 128256, 2, 0), (1504, 160, 256, 15, 17, 17, 1)),
@@ -90,6 +101,7 @@ def test_plans_of_the_benchmark_shapes(args, want):
     p = check_plan(*args, 256)
     got = (p["kernel"], p["block_rows"], p["tile_rows"], p["row_blocks"], p["ranges"], p["parts"], p["k_split"])
     assert got == want
+    assert p["proj_apart"] == (1 if args == (320, 4096, 32000, 3, 4096) else 0)
 
 
 @pytest.mark.parametrize("args", [(0, 4096, 32000, 2, 0, 256), (4, 100, 32000, 2, 0, 256), (4, 4096, 0, 0, 0, 256),
