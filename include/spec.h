@@ -167,13 +167,12 @@ spec_status_t spec_draft_dynamic(spec_model_t* m, const void* state, const int32
  * allocating library routine); it only enqueues kernels on hip_stream.
  *   Limit: the workspace of THIS call (it grows with batch * prod(top_k) and with the widths)
  *   must fit the array: SPEC_ESHAPE otherwise, before anything is enqueued.  A 7B-shaped
- *   model with one sequence and the 5/3/2 tree needs 0.7 MB.
+ *   model with one sequence and the 5/3/2 tree needs 1.2 MB.
  *   The current device must be the model's (SPEC_EINVAL).
  *   Every call on a GPU, from any model and any stream, shares that GPU's array (each GPU the
  *   library runs on holds its own copy until the process ends): calls that overlap in time on
  *   one GPU race, so keep them on one stream or order them with events.  The array keeps the
- *   last call's contents: a call writes every piece before reading it, except a few counters that
- *   are zero when the library is loaded and that every launch using them sets back to zero. */
+ *   last call's contents; a call writes every piece before reading it, nothing needs clearing. */
 spec_status_t spec_draft_static(spec_model_t* m, const void* state, const int32_t* last_tok, int32_t batch,
                                 const int32_t* top_k, int32_t B, int32_t* cand_tokens, float* cand_scores,
                                 int32_t* cand_leaf, void* hip_stream);
