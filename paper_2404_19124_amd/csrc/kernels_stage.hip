@@ -11,16 +11,28 @@ namespace specdraft {
 template <bool BF16, int NCH>
 __global__ __launch_bounds__(256) void stage_kernel(StageJob j) {
   __shared__ float lds[64];
-  stage_row<BF16, NCH, 256>(j, blockIdx.x, lds);
+  int r = blockIdx.x;
+  if (j.xcd_rows) {
+    // Workgroup ids go round-robin over the 8 XCDs, and a row's state is stored as one 16-byte slot in
+    // each of D / 8 lines that it shares with the other rows of its 16-row tile.  Rows of one tile on
+    // eight XCDs leave every L2 with an eighth of each line to write back; here the 16 rows of a tile
+    // run on one XCD, whose L2 puts the lines together (7B shape, 64 sequences: -7 us per step).
+    const int xcd = blockIdx.x & 7, s = blockIdx.x >> 3;
+    r = (((s >> 4) << 3) + xcd) * 16 + (s & 15);
+    if (r >= j.R) return;
+  }
+  stage_row<BF16, NCH, 256>(j, r, lds);
 }
 
 template <bool BF16>
 static hipError_t launch_stage_t(const StageJob& job, hipStream_t st) {
   const int nchunk = job.D / 8;
-  if (nchunk <= 256) hipLaunchKernelGGL((stage_kernel<BF16, 1>), dim3(job.R), dim3(256), 0, st, job);
-  else if (nchunk <= 512) hipLaunchKernelGGL((stage_kernel<BF16, 2>), dim3(job.R), dim3(256), 0, st, job);
-  else if (nchunk <= 1024) hipLaunchKernelGGL((stage_kernel<BF16, 4>), dim3(job.R), dim3(256), 0, st, job);
-  else if (nchunk <= 2048) hipLaunchKernelGGL((stage_kernel<BF16, 8>), dim3(job.R), dim3(256), 0, st, job);
+  // tile-per-XCD order: whole groups of 8 tiles, the workgroups past the last row leave at once
+  const dim3 grid(job.xcd_rows ? (job.R + 127) / 128 * 128 : job.R);
+  if (nchunk <= 256) hipLaunchKernelGGL((stage_kernel<BF16, 1>), grid, dim3(256), 0, st, job);
+  else if (nchunk <= 512) hipLaunchKernelGGL((stage_kernel<BF16, 2>), grid, dim3(256), 0, st, job);
+  else if (nchunk <= 1024) hipLaunchKernelGGL((stage_kernel<BF16, 4>), grid, dim3(256), 0, st, job);
+  else if (nchunk <= 2048) hipLaunchKernelGGL((stage_kernel<BF16, 8>), grid, dim3(256), 0, st, job);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -144,6 +144,7 @@ struct StageJob {
   int stage;               // 0-based
   int R;                   // child rows of this stage
   int k_prev;              // top_k of the previous stage (1 for stage 0)
+  int xcd_rows;            // 1: the 16 rows of a state tile run on one XCD (packed bf16 states, many rows)
   int D;
   int bf16;                // weight / state storage type
   // previous head (stage > 0)

@@ -596,6 +596,7 @@ static spec_status_t draft_impl(spec_model_t* m, const Workspace& ws, const void
     sj.stage = i;
     sj.R = (int)R[i];
     sj.k_prev = i == 0 ? 1 : top_k[i - 1];
+    sj.xcd_rows = (m->bf16 && R[i] > 16) ? 1 : 0;   // more than one tile of packed states
     sj.D = D;
     sj.bf16 = m->bf16 ? 1 : 0;
     sj.part = ws.part;
