@@ -165,17 +165,4 @@ hipError_t launch_copy_probe(const void* src, void* dst, int64_t n16, hipStream_
   return hipGetLastError();
 }
 
-// Fill of n 32-bit words (a kernel rather than a memset node: it may be recorded into a caller's graph).
-__global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ dst, int64_t n, uint32_t value) {
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) dst[i] = value;
-}
-
-hipError_t launch_fill_u32(void* dst, int64_t n, uint32_t value, hipStream_t st) {
-  if (n <= 0) return hipSuccess;
-  const int64_t want = (n + 255) / 256;
-  const int grid = (int)(want > 1024 ? 1024 : want);
-  hipLaunchKernelGGL(fill_u32_kernel, dim3(grid), dim3(256), 0, st, static_cast<uint32_t*>(dst), n, value);
-  return hipGetLastError();
-}
-
 }  // namespace specdraft

@@ -136,8 +136,6 @@ hipError_t launch_row_log_softmax(const float* logits, float* logp, int64_t ld, 
 
 // ---- measurement aid: plain copy of n16 16-byte words -----------------------
 hipError_t launch_copy_probe(const void* src, void* dst, int64_t n16, hipStream_t st);
-// dst[0..n) = value (32-bit words), as a kernel launch
-hipError_t launch_fill_u32(void* dst, int64_t n, uint32_t value, hipStream_t st);
 
 // ---- stage: merge of the previous head's partials + gather + mix + LN + GELU
 struct StageJob {
