@@ -73,22 +73,36 @@ __device__ __forceinline__ void wave_merge_partials_k(const Partials& p, int64_t
         li[u][j] = okj ? i_ : kIdxNone;
       }
     }
+    // softmax pieces of this lane's UN parts: one exponential per part (the fast one: its 1e-6
+    // relative error is far inside what separates float32 from float64 accumulation)
+    float mloc = lm[0];
+#pragma unroll
+    for (int u = 1; u < UN; ++u) mloc = fmaxf(mloc, lm[u]);
+    float sloc = 0.f;
+#pragma unroll
+    for (int u = 0; u < UN; ++u) sloc += lm[u] > SPEC_NEG_INF ? ls[u] * __expf(lm[u] - mloc) : 0.f;
+    if (p0 == 0) {
+      run_m = mloc;
+      run_s = sloc;
+    } else if (mloc > SPEC_NEG_INF) {
+      const float mn = fmaxf(run_m, mloc);
+      run_s = run_s * __expf(run_m - mn) + sloc * __expf(mloc - mn);
+      run_m = mn;
+    }
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      if (lm[u] > SPEC_NEG_INF) {
-        const float mn = fmaxf(run_m, lm[u]);
-        run_s = run_s * expf(run_m - mn) + ls[u] * expf(lm[u] - mn);
-        run_m = mn;
-      }
+      // a part's list is sorted: once an entry does not make the lane's list, the rest do not either
+      bool open = true;
 #pragma unroll
-      for (int j = 0; j < K; ++j)
-        if (j < k && before(lv[u][j], li[u][j], tv[K - 1], ti[K - 1]))
-          list_insert<K>(tv, ti, lv[u][j], li[u][j]);
+      for (int j = 0; j < K; ++j) {
+        open = open && j < k && before(lv[u][j], li[u][j], tv[K - 1], ti[K - 1]);
+        if (open) list_insert<K>(tv, ti, lv[u][j], li[u][j]);
+      }
     }
   }
 
   const float mx = wave_max(run_m);
-  const float sum = wave_sum(run_m > SPEC_NEG_INF ? run_s * expf(run_m - mx) : 0.f);
+  const float sum = wave_sum(run_m > SPEC_NEG_INF ? run_s * __expf(run_m - mx) : 0.f);
   lse = mx + logf(sum);
 
 #pragma unroll

@@ -241,42 +241,67 @@ __device__ __forceinline__ void tree_body(const TreeArgs& j, int q, const int* s
   __threadfence_block();
   __syncthreads();
 
-  const int nleaf = j.B > 0 ? L : 0;
-  for (int leaf = tid; leaf < nleaf; leaf += NT) {
-    float score = 0.f;
-    int64_t local = 0;
-    int stride = L;
-    for (int i = 0; i < n; ++i) {
-      const int k = s_k[i];
-      stride /= k;
-      const int rank = (leaf / stride) % k;
-      score += j.logp[s_off[i] + (s_rbase[i] + local) * s_kw[i] + rank];
-      local = local * k + rank;
+  // A leaf's path, walking up from the leaf: q_{n-1} = leaf, q_{i-1} = q_i / k_i; its node at stage i is
+  // row q_{i-1} of the sequence with rank q_i - q_{i-1} k_i.  at[i] = element of stage i's table.
+  // All of a leaf's table reads are issued together: one round trip, not one per stage.
+  auto path_of = [&](int leaf, int64_t (&at)[kMaxStages]) {
+    int q = leaf;
+#pragma unroll
+    for (int i = kMaxStages - 1; i >= 0; --i) {
+      at[i] = 0;
+      if (i < n) {
+        const int k = s_k[i];
+        const int up = q / k;
+        at[i] = s_off[i] + (s_rbase[i] + up) * s_kw[i] + (q - up * k);
+        q = up;
+      }
     }
+  };
+  const int nleaf = j.B > 0 ? L : 0;
+  const bool one_pass = nleaf <= NT;   // every thread has at most one leaf: its tokens stay in registers
+  int32_t tk[kMaxStages];
+  for (int leaf = tid; leaf < nleaf; leaf += NT) {
+    int64_t at[kMaxStages];
+    path_of(leaf, at);
+    float lp[kMaxStages];
+#pragma unroll
+    for (int i = 0; i < kMaxStages; ++i) {
+      lp[i] = i < n ? j.logp[at[i]] : 0.f;
+      tk[i] = (one_pass && i < n) ? j.tok[at[i]] : 0;
+    }
+    float score = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxStages; ++i)
+      if (i < n) score += lp[i];
     sc[leaf] = score;
   }
+  // (the ranking reads four scores at a time: fill the last group)
+  if (tid < 4 && (nleaf & ~3) + tid >= nleaf && (nleaf & ~3) + tid < kMaxLeaves) sc[(nleaf & ~3) + tid] = SPEC_NEG_INF;
   __syncthreads();
 
   for (int leaf = tid; leaf < nleaf; leaf += NT) {
     const float s = sc[leaf];
     int pos = 0;
-    for (int o = 0; o < L; ++o) {
-      const float so = sc[o];
-      pos += ((so > s) || (so == s && o < leaf)) ? 1 : 0;
+    for (int o = 0; o < nleaf; o += 4) {
+      const float4 so = *reinterpret_cast<const float4*>(sc + o);
+      pos += ((so.x > s) || (so.x == s && o < leaf)) ? 1 : 0;
+      pos += ((so.y > s) || (so.y == s && o + 1 < leaf)) ? 1 : 0;
+      pos += ((so.z > s) || (so.z == s && o + 2 < leaf)) ? 1 : 0;
+      pos += ((so.w > s) || (so.w == s && o + 3 < leaf)) ? 1 : 0;
     }
     if (pos < j.B) {
       const int64_t c = (int64_t)q * j.B_pad + pos;
       j.cand_leaf[c] = leaf;
       j.cand_scores[c] = s;
-      int64_t local = 0;
-      int stride = L;
-      for (int i = 0; i < n; ++i) {
-        const int k = s_k[i];
-        stride /= k;
-        const int rank = (leaf / stride) % k;
-        j.cand_tokens[c * n + i] = j.tok[s_off[i] + (s_rbase[i] + local) * s_kw[i] + rank];
-        local = local * k + rank;
+      if (!one_pass) {
+        int64_t at[kMaxStages];
+        path_of(leaf, at);
+#pragma unroll
+        for (int i = 0; i < kMaxStages; ++i) tk[i] = i < n ? j.tok[at[i]] : 0;
       }
+#pragma unroll
+      for (int i = 0; i < kMaxStages; ++i)
+        if (i < n) j.cand_tokens[c * n + i] = tk[i];
     }
   }
   // slots past this sequence's candidates: padding
@@ -289,7 +314,8 @@ __device__ __forceinline__ void tree_body(const TreeArgs& j, int q, const int* s
 }
 
 // Fills the per-sequence arguments of tree_body for sequence q from a TreeJob: thread 0 .. n-1 write
-// the LDS arrays, every thread computes the scalars.  Call with all threads, then __syncthreads().
+// the LDS arrays, every thread computes the scalars.  Call with all threads; the LDS arrays are valid after the
+// next workgroup barrier (tree_body reads them only behind the one that ends its merge).
 __device__ __forceinline__ void tree_args_for_sequence(const TreeJob& j, int q, TreeArgs& a, int* s_k, int64_t* s_off,
                                                        int64_t* s_rbase, int* s_kw) {
   const int tid = opaque_tid();
