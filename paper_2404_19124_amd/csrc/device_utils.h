@@ -88,18 +88,39 @@ __device__ __forceinline__ float row16_max(float x) {
   x = fmaxf(x, dpp_f<kDppMirror>(x));
   return x;
 }
-template <int CTRL>
-__device__ __forceinline__ void best_step(float& v, int32_t& i) {
-  const float ov = dpp_f<CTRL>(v);
-  const int32_t oi = dpp_i<CTRL>(i);
-  if (before(ov, oi, v, i)) { v = ov; i = oi; }
+// (value, index) pairs are reduced as ONE 64-bit key: high word = the float mapped to an unsigned
+// integer of the same order (zeros of both signs alike, NaN below everything: it never wins, as
+// under before()), low word = ~index (smaller index = larger key).  A reduction step is then two
+// DPP moves, one 64-bit compare and two selects; compares of the pair in three pieces with the
+// mask logic on the scalar unit took twice the instructions and a round trip between the units.
+__device__ __forceinline__ uint64_t best_key(float v, int32_t i) {
+  const uint32_t u = __float_as_uint(v + 0.0f);
+  const uint32_t k = u ^ (static_cast<uint32_t>(static_cast<int32_t>(u) >> 31) | 0x80000000u);
+  return (static_cast<uint64_t>(v != v ? 0u : k) << 32) | static_cast<uint32_t>(~i);
+}
+__device__ __forceinline__ void best_unkey(uint64_t key, float& v, int32_t& i) {
+  const uint32_t k = static_cast<uint32_t>(key >> 32);
+  v = __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
+  i = static_cast<int32_t>(~static_cast<uint32_t>(key));
+}
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ uint64_t key_step(uint64_t key) {
+  // rows outside ROW_MASK keep their own key (old = source): the step is then a no-op for them
+  const int32_t hi = static_cast<int32_t>(key >> 32), lo = static_cast<int32_t>(key);
+  const uint32_t oh = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(hi, hi, CTRL, ROW_MASK, 0xf, false));
+  const uint32_t ol = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(lo, lo, CTRL, ROW_MASK, 0xf, false));
+  const uint64_t other = (static_cast<uint64_t>(oh) << 32) | ol;
+  return other > key ? other : key;
+}
+__device__ __forceinline__ uint64_t row16_best_key(uint64_t key) {
+  key = key_step<kDppXor1>(key);
+  key = key_step<kDppXor2>(key);
+  key = key_step<kDppHalfMirror>(key);
+  return key_step<kDppMirror>(key);
 }
 // best (value, index) over each row of 16 lanes
 __device__ __forceinline__ void row16_best(float& v, int32_t& i) {
-  best_step<kDppXor1>(v, i);
-  best_step<kDppXor2>(v, i);
-  best_step<kDppHalfMirror>(v, i);
-  best_step<kDppMirror>(v, i);
+  best_unkey(row16_best_key(best_key(v, i)), v, i);
 }
 
 __device__ __forceinline__ float wave_sum(float x) {
@@ -110,19 +131,19 @@ __device__ __forceinline__ float wave_max(float x) {
   x = row16_max(x);
   return fmaxf(fmaxf(lane_f(x, 0), lane_f(x, 16)), fmaxf(lane_f(x, 32), lane_f(x, 48)));
 }
-// best (value, index) over the wave; every lane gets the result
+
+// best (value, index) over the wave; every lane gets the result.  The four row results are
+// combined on DPP row broadcasts (lane 15 of a row into the next row, then lane 31 into the
+// upper half: lane 63 ends with the wave's best) and read back once.
+constexpr int kDppRowBcast15 = 0x142;
+constexpr int kDppRowBcast31 = 0x143;
 __device__ __forceinline__ void wave_best(float& v, int32_t& i) {
-  row16_best(v, i);
-  float bv = lane_f(v, 0);
-  int32_t bi = __builtin_amdgcn_readlane(i, 0);
-#pragma unroll
-  for (int r = 16; r < 64; r += 16) {
-    const float ov = lane_f(v, r);
-    const int32_t oi = __builtin_amdgcn_readlane(i, r);
-    if (before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-  }
-  v = bv;
-  i = bi;
+  uint64_t key = row16_best_key(best_key(v, i));
+  key = key_step<kDppRowBcast15, 0xa>(key);
+  key = key_step<kDppRowBcast31, 0xc>(key);
+  const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int32_t>(key >> 32), 63));
+  const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int32_t>(key), 63));
+  best_unkey((static_cast<uint64_t>(hi) << 32) | lo, v, i);
 }
 
 // Block-wide helpers for blocks of NT threads (NT multiple of 64, <= 1024).

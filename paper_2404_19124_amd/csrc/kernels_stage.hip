@@ -10,7 +10,7 @@ namespace specdraft {
 // NCH = 8-element chunks per thread held in registers (D <= NCH * 2048).
 template <bool BF16, int NCH>
 __global__ __launch_bounds__(256) void stage_kernel(StageJob j) {
-  __shared__ float lds[64];
+  __shared__ float lds[32 + kMergeLds];
   int r = blockIdx.x;
   if (j.xcd_rows) {
     // Workgroup ids go round-robin over the 8 XCDs, and a row's state is stored as one 16-byte slot in
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(NT) void tree_kernel(TreeJob j) {
   __shared__ __align__(16) float sc[kMaxLeaves];
   __shared__ int s_k[kMaxStages], s_kw[kMaxStages];
   __shared__ int64_t s_off[kMaxStages], s_rbase[kMaxStages];
-  __shared__ float merge_lds[32 * (NT / 256)];
+  __shared__ float merge_lds[kMergeLds * (NT / 256)];
   TreeArgs a;
   tree_args_for_sequence(j, blockIdx.x, a, s_k, s_off, s_rbase, s_kw);
   // (no barrier here: the merge at the head of tree_body reads none of the LDS arrays and ends in one, so a

@@ -130,12 +130,17 @@ __device__ __forceinline__ void wave_merge_partials_k(const Partials& p, int64_t
 
 // The same merge done by a group of 256 consecutive threads for ONE row: with at most
 // 256 parts every thread holds exactly one part's (already sorted) list, so nothing has
-// to be inserted; the k results are popped with one wave reduction plus a 4-entry
-// exchange through LDS per round.  A workgroup of 256 * n threads runs n such groups
-// side by side (each on its own row, or all on the same one): the function contains
+// to be inserted.  Two levels, ONE exchange: every wave reduces its 64 parts to its own
+// (max, sum-exp, k best) with wave-wide reductions only, the four waves' results go
+// through LDS behind a single barrier, and every thread merges the four sorted lists.
+// (A pop per round across the whole group - one barrier and one LDS exchange per result -
+// took 0.65 us per round on the batch-1 chain.)  A workgroup of 256 * n threads runs n such
+// groups side by side (each on its own row, or all on the same one): the function contains
 // workgroup barriers, so EVERY thread of the workgroup must call it, with the same k
 // and nparts; every thread receives its group's result.  `lds` is the group's own
-// scratch of 32 words.
+// scratch of kMergeLds words.
+constexpr int kMergeWave = 2 + 2 * kMaxTopK;   // words per wave: max, sum-exp, k values, k indices
+constexpr int kMergeLds = 4 * kMergeWave;
 template <int K>
 __device__ __forceinline__ void group_merge_partials_k(const Partials& p, int64_t row, int nparts, int k,
                                                      float (&out_val)[kMaxTopK], int32_t (&out_idx)[kMaxTopK],
@@ -168,7 +173,7 @@ __device__ __forceinline__ void group_merge_partials_k(const Partials& p, int64_
     const float m_ = pm[part], s_ = ps[part];
     if (m_ > SPEC_NEG_INF) {
       const float mn = fmaxf(run_m, m_);
-      run_s = run_s * expf(run_m - mn) + s_ * expf(m_ - mn);
+      run_s = run_s * __expf(run_m - mn) + s_ * __expf(m_ - mn);
       run_m = mn;
     }
     for (int j = 0; j < k; ++j) {
@@ -178,49 +183,82 @@ __device__ __forceinline__ void group_merge_partials_k(const Partials& p, int64_
     }
   }
 
-  float* red = lds;                                   // [2][4] reductions of the group's four waves
-  float* xv = lds + 8;                                // [2][4] round exchange, values
-  int32_t* xi = reinterpret_cast<int32_t*>(lds + 16); // [2][4] round exchange, indices
+  // ---- this wave's 64 parts
   const float wm = wave_max(run_m);
-  __syncthreads();                                    // scratch may still be read from an earlier call
-  if (lane == 0) red[w] = wm;
-  __syncthreads();
-  const float mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-  const float wsum = wave_sum(run_m > SPEC_NEG_INF ? run_s * expf(run_m - mx) : 0.f);
-  if (lane == 0) red[4 + w] = wsum;
-  __syncthreads();
-  lse = mx + logf((red[4] + red[5]) + (red[6] + red[7]));
-
-#pragma unroll
-  for (int j = 0; j < kMaxTopK; ++j) {
-    out_val[j] = SPEC_NEG_INF;
-    out_idx[j] = kIdxNone;
-  }
+  const float wsum = wave_sum(run_m > SPEC_NEG_INF ? run_s * __expf(run_m - wm) : 0.f);
+  float wv[K];
+  int32_t wi[K];
 #pragma unroll
   for (int j = 0; j < K; ++j) {
+    wv[j] = SPEC_NEG_INF;
+    wi[j] = kIdxNone;
     if (j < k) {
       float bv = tv[0];
       int32_t bi = ti[0];
       wave_best(bv, bi);
-      const int buf = j & 1;       // double-buffered: one barrier per round
-      if (lane == 0) { xv[buf * 4 + w] = bv; xi[buf * 4 + w] = bi; }
-      __syncthreads();
-      bv = xv[buf * 4];
-      bi = xi[buf * 4];
-#pragma unroll
-      for (int q = 1; q < 4; ++q) {
-        const float ov = xv[buf * 4 + q];
-        const int32_t oi = xi[buf * 4 + q];
-        if (before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-      }
       if (ti[0] == bi && tv[0] == bv) {  // the owner of the winner pops it
 #pragma unroll
         for (int q = 0; q + 1 < K; ++q) { tv[q] = tv[q + 1]; ti[q] = ti[q + 1]; }
         tv[K - 1] = SPEC_NEG_INF;
         ti[K - 1] = kIdxNone;
       }
-      out_val[j] = bv;
-      out_idx[j] = bi;
+      wv[j] = bv;
+      wi[j] = bi;
+    }
+  }
+
+  // ---- the four waves' results through LDS
+  float* mine = lds + w * kMergeWave;
+  __syncthreads();                                    // scratch may still be read from an earlier call
+  if (lane == 0) {
+    mine[0] = wm;
+    mine[1] = wsum;
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      mine[2 + j] = wv[j];
+      reinterpret_cast<int32_t*>(mine)[2 + kMaxTopK + j] = wi[j];
+    }
+  }
+  __syncthreads();
+  float m4[4], s4[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) { m4[q] = lds[q * kMergeWave]; s4[q] = lds[q * kMergeWave + 1]; }
+  const float mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
+  float sum = 0.f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) sum += m4[q] > SPEC_NEG_INF ? s4[q] * __expf(m4[q] - mx) : 0.f;
+  lse = mx + logf(sum);
+
+#pragma unroll
+  for (int j = 0; j < kMaxTopK; ++j) {
+    out_val[j] = SPEC_NEG_INF;
+    out_idx[j] = kIdxNone;
+  }
+  // four sorted lists, as 64-bit keys in registers (one batch of LDS reads): only their heads compete;
+  // the list whose head won moves up by one (keys are unique: every candidate has its own token)
+  uint64_t lk[4][K];
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int t = 0; t < K; ++t)
+      lk[q][t] = best_key(lds[q * kMergeWave + 2 + t],
+                          reinterpret_cast<const int32_t*>(lds)[q * kMergeWave + 2 + kMaxTopK + t]);
+#pragma unroll
+  for (int j = 0; j < K; ++j) {
+    if (j < k) {
+      uint64_t best = lk[0][0];
+#pragma unroll
+      for (int q = 1; q < 4; ++q) best = lk[q][0] > best ? lk[q][0] : best;
+      best_unkey(best, out_val[j], out_idx[j]);
+      if (j + 1 < k) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const bool won = lk[q][0] == best;
+#pragma unroll
+          for (int t = 0; t + 1 < K; ++t) lk[q][t] = won ? lk[q][t + 1] : lk[q][t];
+          lk[q][K - 1] = won ? best_key(SPEC_NEG_INF, kIdxNone) : lk[q][K - 1];
+        }
+      }
     }
   }
 }

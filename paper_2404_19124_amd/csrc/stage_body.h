@@ -12,13 +12,13 @@ namespace specdraft {
 // partial results are merged here (every sibling repeats the small merge, which saves
 // a separate launch on the latency-critical batch-1 chain).
 // NCH = 8-element chunks per thread held in registers (D <= NCH * NT * 8).
-// `lds`: (NT / 256) * 32 + 32 words of scratch.  Contains workgroup barriers.
+// `lds`: 32 + (NT / 256) * kMergeLds words of scratch.  Contains workgroup barriers.
 // States are stored as whole 16-byte slots; the L2 gathers the eight rows that share a 128-byte line.
 template <bool BF16, int NCH, int NT>
 __device__ __forceinline__ void stage_row(const StageJob& j, int r, float* lds) {
   float* scratch = lds;                 // NT / 64 <= 16 words
   const int tid = opaque_tid(), lane = tid & 63;
-  float* merge_lds = lds + 32 + (tid >> 8) * 32;
+  float* merge_lds = lds + 32 + (tid >> 8) * kMergeLds;
   int parent = r / j.k_prev, rank = r - parent * j.k_prev;
   if (j.row_parent) {  // per-sequence trees: the host laid the rows out
     parent = j.row_parent[r];
@@ -184,7 +184,7 @@ struct TreeArgs {
 // s_k / s_off / s_rbase / s_kw: per stage, in LDS (indexing kernel arguments with a run-time stage
 // number would make the compiler spill the argument block to scratch): this sequence's branching,
 // the table's element offset, this sequence's first row, the table's width.
-// sc: kMaxLeaves floats of LDS; merge_lds: (NT / 256) * 32 words.
+// sc: kMaxLeaves floats of LDS; merge_lds: (NT / 256) * kMergeLds words.
 // KWAVE: widest kw_last merged one row per wave (register-hungry for wide lists: a wave
 // of a 1024-thread workgroup has 128 registers); wider ones are merged one row per
 // 256-thread group.  Contains workgroup barriers.
@@ -228,7 +228,7 @@ __device__ __forceinline__ void tree_body(const TreeArgs& j, int q, const int* s
       float v[kMaxTopK];
       int32_t ix[kMaxTopK];
       float lse;
-      group_merge_partials(j.part, row, j.nparts, kw, v, ix, lse, merge_lds + grp * 32);
+      group_merge_partials(j.part, row, j.nparts, kw, v, ix, lse, merge_lds + grp * kMergeLds);
 #pragma unroll
       for (int t = 0; t < kMaxTopK; ++t)
         if (live && gl == t && t < kw) {
