@@ -137,13 +137,17 @@ __device__ __forceinline__ float wave_max(float x) {
 // upper half: lane 63 ends with the wave's best) and read back once.
 constexpr int kDppRowBcast15 = 0x142;
 constexpr int kDppRowBcast31 = 0x143;
-__device__ __forceinline__ void wave_best(float& v, int32_t& i) {
-  uint64_t key = row16_best_key(best_key(v, i));
+// largest key over the wave; every lane gets it
+__device__ __forceinline__ uint64_t wave_best_key(uint64_t key) {
+  key = row16_best_key(key);
   key = key_step<kDppRowBcast15, 0xa>(key);
   key = key_step<kDppRowBcast31, 0xc>(key);
   const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int32_t>(key >> 32), 63));
   const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int32_t>(key), 63));
-  best_unkey((static_cast<uint64_t>(hi) << 32) | lo, v, i);
+  return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+__device__ __forceinline__ void wave_best(float& v, int32_t& i) {
+  best_unkey(wave_best_key(best_key(v, i)), v, i);
 }
 
 // Block-wide helpers for blocks of NT threads (NT multiple of 64, <= 1024).

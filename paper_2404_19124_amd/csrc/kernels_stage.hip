@@ -51,15 +51,17 @@ hipError_t launch_stage(const StageJob& job, hipStream_t st) {
 // last-stage top-k <= 4 (KWAVE = 4): sixteen rows per pass, one pass for the paper's trees.
 template <int NT, int KWAVE>
 __global__ __launch_bounds__(NT) void tree_kernel(TreeJob j) {
-  __shared__ __align__(16) float sc[kMaxLeaves];
+  __shared__ __align__(16) uint64_t sk[kMaxLeaves];
   __shared__ int s_k[kMaxStages], s_kw[kMaxStages];
   __shared__ int64_t s_off[kMaxStages], s_rbase[kMaxStages];
   __shared__ float merge_lds[kMergeLds * (NT / 256)];
+  __shared__ int32_t c_tok[kMaxLeaves];
+  __shared__ float c_logp[kMaxLeaves];
   TreeArgs a;
   tree_args_for_sequence(j, blockIdx.x, a, s_k, s_off, s_rbase, s_kw);
-  // (no barrier here: the merge at the head of tree_body reads none of the LDS arrays and ends in one, so a
-  // wave starts its partial loads while the later waves of the workgroup are still being launched)
-  tree_body<NT, KWAVE>(a, blockIdx.x, s_k, s_off, s_rbase, s_kw, sc, merge_lds);
+  // (no barrier here: a wave reads back only what it wrote itself until the merge in tree_body ends in one,
+  // so it starts its loads while the later waves of the workgroup are still being launched)
+  tree_body<NT, KWAVE>(a, blockIdx.x, s_k, s_off, s_rbase, s_kw, sk, merge_lds, c_tok, c_logp);
 }
 
 hipError_t launch_tree(const TreeJob& job, hipStream_t st) {

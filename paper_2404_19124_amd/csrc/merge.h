@@ -43,10 +43,11 @@ __device__ __forceinline__ void wave_merge_partials_k(const Partials& p, int64_t
   const float* pv = p.val + row * (int64_t)nparts * k;
   const int32_t* pi = p.idx + row * (int64_t)nparts * k;
 
-  float tv[K];
-  int32_t ti[K];
+  // the lane's list, as 64-bit keys (best_key): sorted, empty slots hold the key of (-inf, none)
+  const uint64_t kEmpty = best_key(SPEC_NEG_INF, kIdxNone);
+  uint64_t tk[K];
 #pragma unroll
-  for (int q = 0; q < K; ++q) { tv[q] = SPEC_NEG_INF; ti[q] = kIdxNone; }
+  for (int q = 0; q < K; ++q) tk[q] = kEmpty;
   float run_m = SPEC_NEG_INF, run_s = 0.f;
 
   constexpr int UN = 4;
@@ -89,14 +90,20 @@ __device__ __forceinline__ void wave_merge_partials_k(const Partials& p, int64_t
       run_s = run_s * __expf(run_m - mn) + sloc * __expf(mloc - mn);
       run_m = mn;
     }
+    // branch-free insertion: a chain of compare-exchanges down the list (an entry that does not
+    // belong, the empty key included, falls through and changes nothing)
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      // a part's list is sorted: once an entry does not make the lane's list, the rest do not either
-      bool open = true;
 #pragma unroll
       for (int j = 0; j < K; ++j) {
-        open = open && j < k && before(lv[u][j], li[u][j], tv[K - 1], ti[K - 1]);
-        if (open) list_insert<K>(tv, ti, lv[u][j], li[u][j]);
+        uint64_t x = best_key(lv[u][j], li[u][j]);
+#pragma unroll
+        for (int q = 0; q < K; ++q) {
+          const bool gt = x > tk[q];
+          const uint64_t lower = gt ? tk[q] : x;
+          tk[q] = gt ? x : tk[q];
+          x = lower;
+        }
       }
     }
   }
@@ -113,17 +120,12 @@ __device__ __forceinline__ void wave_merge_partials_k(const Partials& p, int64_t
 #pragma unroll
   for (int j = 0; j < K; ++j) {
     if (j < k) {
-      float bv = tv[0];
-      int32_t bi = ti[0];
-      wave_best(bv, bi);
-      if (ti[0] == bi && tv[0] == bv) {  // the owner of the winner pops it
+      const uint64_t best = wave_best_key(tk[0]);
+      const bool won = tk[0] == best;   // the owner of the winner pops it (keys of real entries are unique)
 #pragma unroll
-        for (int q = 0; q + 1 < K; ++q) { tv[q] = tv[q + 1]; ti[q] = ti[q + 1]; }
-        tv[K - 1] = SPEC_NEG_INF;
-        ti[K - 1] = kIdxNone;
-      }
-      out_val[j] = bv;
-      out_idx[j] = bi;
+      for (int q = 0; q + 1 < K; ++q) tk[q] = won ? tk[q + 1] : tk[q];
+      tk[K - 1] = won ? kEmpty : tk[K - 1];
+      best_unkey(best, out_val[j], out_idx[j]);
     }
   }
 }

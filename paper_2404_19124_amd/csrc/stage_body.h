@@ -184,19 +184,65 @@ struct TreeArgs {
 // s_k / s_off / s_rbase / s_kw: per stage, in LDS (indexing kernel arguments with a run-time stage
 // number would make the compiler spill the argument block to scratch): this sequence's branching,
 // the table's element offset, this sequence's first row, the table's width.
-// sc: kMaxLeaves floats of LDS; merge_lds: (NT / 256) * kMergeLds words.
+// sk: kMaxLeaves 64-bit words of LDS (the leaves' scores as keys, see best_key); merge_lds: (NT / 256) * kMergeLds words; c_tok / c_logp: kMaxLeaves words
+// each, the last stage's tables of this sequence for the leaf scores (the tables in memory are written all
+// the same: the debug outputs and the caller's next step read them).
 // KWAVE: widest kw_last merged one row per wave (register-hungry for wide lists: a wave
 // of a 1024-thread workgroup has 128 registers); wider ones are merged one row per
 // 256-thread group.  Contains workgroup barriers.
 template <int NT, int KWAVE>
 __device__ __forceinline__ void tree_body(const TreeArgs& j, int q, const int* s_k, const int64_t* s_off,
-                                          const int64_t* s_rbase, const int* s_kw, float* sc, float* merge_lds) {
+                                          const int64_t* s_rbase, const int* s_kw, uint64_t* sk, float* merge_lds,
+                                          int32_t* c_tok, float* c_logp) {
   const int tid = opaque_tid(), lane = tid & 63, wave = tid >> 6;
   const int n = j.n, L = j.L, kw = j.kw_last;
   const int rows_last = j.B > 0 ? L / j.k_last : 0;
+  const int nleaf = j.B > 0 ? L : 0;
+
+  // A leaf's path, walking up from the leaf: q_{n-1} = leaf, q_{i-1} = q_i / k_i; its node at stage i is
+  // row q_{i-1} of the sequence with rank q_i - q_{i-1} k_i.  at[i] = element of stage i's table.
+  // All of a leaf's table reads are issued together: one round trip, not one per stage.
+  auto path_of = [&](int leaf, int64_t (&at)[kMaxStages]) {
+    int q = leaf;
+#pragma unroll
+    for (int i = kMaxStages - 1; i >= 0; --i) {
+      at[i] = 0;
+      if (i < n) {
+        const int k = s_k[i];
+        // q < 4096, k <= 8: the float quotient of q + 1/2 is farther from an integer than its rounding error
+        const int up = (int)(((float)q + 0.5f) * __frcp_rn((float)k));
+        at[i] = s_off[i] + (s_rbase[i] + up) * s_kw[i] + (q - up * k);
+        q = up;
+      }
+    }
+  };
+  // One leaf per thread and the last stage's tables small enough for LDS (the paper's trees): a leaf's
+  // entries of the EARLIER stages are requested before the merge and arrive under it; the last stage's
+  // come from the merge through LDS.  The leaf scores then wait for no memory at all.
+  const bool one_pass = nleaf <= NT;   // every thread has at most one leaf: its tokens stay in registers
+  constexpr int kEarly = 3;            // earlier stages whose entries a thread holds across the merge (registers)
+  const bool early = one_pass && n - 1 <= kEarly && (int64_t)rows_last * kw <= kMaxLeaves;
+  float lp_e[kEarly];
+  int32_t tk_e[kEarly];
+  int last_at = 0;
+  if (early && tid < nleaf) {
+    int64_t at[kMaxStages];
+    path_of(tid, at);
+#pragma unroll
+    for (int i = 0; i < kMaxStages; ++i) {
+      if (i < kEarly) {
+        lp_e[i] = i < n - 1 ? j.logp[at[i]] : 0.f;
+        tk_e[i] = i < n - 1 ? j.tok[at[i]] : 0;
+      }
+      if (i == n - 1) last_at = (int)(at[i] - (j.off_last + j.rbase_last * kw));
+    }
+  }
 
   if (kw <= KWAVE) {
-    for (int rl = wave; rl < rows_last; rl += NT / 64) {
+    // (the first wave has just spent its time on the leaves' paths: it stays out of the merge when the
+    // other waves cover the rows in one pass)
+    const int w0 = (early && rows_last <= NT / 64 - 1) ? 1 : 0;
+    for (int rl = wave - w0; rl >= 0 && rl < rows_last; rl += NT / 64 - w0) {
       const int64_t row = j.rbase_last + rl;
       float v[kMaxTopK];
       int32_t ix[kMaxTopK];
@@ -216,6 +262,10 @@ __device__ __forceinline__ void tree_body(const TreeArgs& j, int q, const int* s
         if (lane == t && t < kw) {
           j.tok[j.off_last + row * kw + t] = ix[t];
           j.logp[j.off_last + row * kw + t] = v[t] - lse;
+          if (early) {
+            c_tok[rl * kw + t] = ix[t];
+            c_logp[rl * kw + t] = v[t] - lse;
+          }
         }
       if (lane == 0) j.lse[j.row_off_last + row] = lse;
     }
@@ -234,6 +284,10 @@ __device__ __forceinline__ void tree_body(const TreeArgs& j, int q, const int* s
         if (live && gl == t && t < kw) {
           j.tok[j.off_last + row * kw + t] = ix[t];
           j.logp[j.off_last + row * kw + t] = v[t] - lse;
+          if (early) {
+            c_tok[rl * kw + t] = ix[t];
+            c_logp[rl * kw + t] = v[t] - lse;
+          }
         }
       if (live && gl == 0) j.lse[j.row_off_last + row] = lse;
     }
@@ -241,54 +295,58 @@ __device__ __forceinline__ void tree_body(const TreeArgs& j, int q, const int* s
   __threadfence_block();
   __syncthreads();
 
-  // A leaf's path, walking up from the leaf: q_{n-1} = leaf, q_{i-1} = q_i / k_i; its node at stage i is
-  // row q_{i-1} of the sequence with rank q_i - q_{i-1} k_i.  at[i] = element of stage i's table.
-  // All of a leaf's table reads are issued together: one round trip, not one per stage.
-  auto path_of = [&](int leaf, int64_t (&at)[kMaxStages]) {
-    int q = leaf;
-#pragma unroll
-    for (int i = kMaxStages - 1; i >= 0; --i) {
-      at[i] = 0;
-      if (i < n) {
-        const int k = s_k[i];
-        const int up = q / k;
-        at[i] = s_off[i] + (s_rbase[i] + up) * s_kw[i] + (q - up * k);
-        q = up;
-      }
-    }
-  };
-  const int nleaf = j.B > 0 ? L : 0;
-  const bool one_pass = nleaf <= NT;   // every thread has at most one leaf: its tokens stay in registers
   int32_t tk[kMaxStages];
-  for (int leaf = tid; leaf < nleaf; leaf += NT) {
-    int64_t at[kMaxStages];
-    path_of(leaf, at);
-    float lp[kMaxStages];
+  if (early) {
+    if (tid < nleaf) {
+      float score = 0.f;   // added in stage order
 #pragma unroll
-    for (int i = 0; i < kMaxStages; ++i) {
-      lp[i] = i < n ? j.logp[at[i]] : 0.f;
-      tk[i] = (one_pass && i < n) ? j.tok[at[i]] : 0;
+      for (int i = 0; i < kMaxStages; ++i) {
+        tk[i] = 0;
+        if (i < kEarly && i < n - 1) {
+          score += lp_e[i];
+          tk[i] = tk_e[i];
+        }
+        if (i == n - 1) {
+          score += c_logp[last_at];
+          tk[i] = c_tok[last_at];
+        }
+      }
+      sk[tid] = best_key(score, tid);
     }
-    float score = 0.f;
+  } else {
+    for (int leaf = tid; leaf < nleaf; leaf += NT) {
+      int64_t at[kMaxStages];
+      path_of(leaf, at);
+      float lp[kMaxStages];
 #pragma unroll
-    for (int i = 0; i < kMaxStages; ++i)
-      if (i < n) score += lp[i];
-    sc[leaf] = score;
+      for (int i = 0; i < kMaxStages; ++i) {
+        lp[i] = i < n ? j.logp[at[i]] : 0.f;
+        tk[i] = (one_pass && i < n) ? j.tok[at[i]] : 0;
+      }
+      float score = 0.f;
+#pragma unroll
+      for (int i = 0; i < kMaxStages; ++i)
+        if (i < n) score += lp[i];
+      sk[leaf] = best_key(score, leaf);
+    }
   }
-  // (the ranking reads four scores at a time: fill the last group)
-  if (tid < 4 && (nleaf & ~3) + tid >= nleaf && (nleaf & ~3) + tid < kMaxLeaves) sc[(nleaf & ~3) + tid] = SPEC_NEG_INF;
+  // (the ranking reads two keys at a time: fill the last pair)
+  if (tid == 0 && (nleaf & 1) && nleaf < kMaxLeaves) sk[nleaf] = 0;
   __syncthreads();
 
+  // rank of a leaf = number of leaves before it in (score, then smaller leaf index): one 64-bit compare each
   for (int leaf = tid; leaf < nleaf; leaf += NT) {
-    const float s = sc[leaf];
+    const uint64_t mine = sk[leaf];
     int pos = 0;
-    for (int o = 0; o < nleaf; o += 4) {
-      const float4 so = *reinterpret_cast<const float4*>(sc + o);
-      pos += ((so.x > s) || (so.x == s && o < leaf)) ? 1 : 0;
-      pos += ((so.y > s) || (so.y == s && o + 1 < leaf)) ? 1 : 0;
-      pos += ((so.z > s) || (so.z == s && o + 2 < leaf)) ? 1 : 0;
-      pos += ((so.w > s) || (so.w == s && o + 3 < leaf)) ? 1 : 0;
+#pragma unroll 4
+    for (int o = 0; o < nleaf; o += 2) {
+      const uint64_t k0 = sk[o], k1 = sk[o + 1];
+      pos += k0 > mine ? 1 : 0;
+      pos += k1 > mine ? 1 : 0;
     }
+    float s;
+    int32_t self;
+    best_unkey(mine, s, self);
     if (pos < j.B) {
       const int64_t c = (int64_t)q * j.B_pad + pos;
       j.cand_leaf[c] = leaf;
@@ -313,9 +371,9 @@ __device__ __forceinline__ void tree_body(const TreeArgs& j, int q, const int* s
   }
 }
 
-// Fills the per-sequence arguments of tree_body for sequence q from a TreeJob: thread 0 .. n-1 write
-// the LDS arrays, every thread computes the scalars.  Call with all threads; the LDS arrays are valid after the
-// next workgroup barrier (tree_body reads them only behind the one that ends its merge).
+// Fills the per-sequence arguments of tree_body for sequence q from a TreeJob: lanes 0 .. n-1 of EVERY wave
+// write the LDS arrays (the same values: a wave may then read them back without a workgroup barrier, its own
+// LDS accesses execute in order), every thread computes the scalars.  Call with all threads.
 __device__ __forceinline__ void tree_args_for_sequence(const TreeJob& j, int q, TreeArgs& a, int* s_k, int64_t* s_off,
                                                        int64_t* s_rbase, int* s_kw) {
   const int tid = opaque_tid();
@@ -336,7 +394,7 @@ __device__ __forceinline__ void tree_args_for_sequence(const TreeJob& j, int q, 
       const int k = d ? d[i] : j.top_k[i];
       const int64_t rbase = d ? (int64_t)d[n + i] : (int64_t)q * cnt;
       if (d) a.L *= k;
-      if (tid == i) { s_k[i] = k; s_off[i] = j.off[i]; s_rbase[i] = rbase; s_kw[i] = j.kstride[i]; }
+      if ((tid & 63) == i) { s_k[i] = k; s_off[i] = j.off[i]; s_rbase[i] = rbase; s_kw[i] = j.kstride[i]; }
       if (i == n - 1) {
         a.k_last = k; a.kw_last = j.kstride[i]; a.off_last = j.off[i]; a.row_off_last = j.row_off[i];
         a.rbase_last = rbase;
