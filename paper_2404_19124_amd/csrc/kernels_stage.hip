@@ -7,10 +7,10 @@
 
 namespace specdraft {
 
-// NCH = 8-element chunks per thread held in registers (D <= NCH * 2048).
-template <bool BF16, int NCH>
-__global__ __launch_bounds__(256) void stage_kernel(StageJob j) {
-  __shared__ float lds[32 + kMergeLds];
+// NCH = 8-element chunks per thread held in registers (D <= NCH * NT * 8).
+template <bool BF16, int NCH, int NT>
+__global__ __launch_bounds__(NT) void stage_kernel(StageJob j) {
+  __shared__ float lds[32 + (NT / 256) * kMergeLds];
   int r = blockIdx.x;
   if (j.xcd_rows) {
     // Workgroup ids go round-robin over the 8 XCDs, and a row's state is stored as one 16-byte slot in
@@ -21,7 +21,7 @@ __global__ __launch_bounds__(256) void stage_kernel(StageJob j) {
     r = (((s >> 4) << 3) + xcd) * 16 + (s & 15);
     if (r >= j.R) return;
   }
-  stage_row<BF16, NCH, 256>(j, r, lds);
+  stage_row<BF16, NCH, NT>(j, r, lds);
 }
 
 template <bool BF16>
@@ -29,10 +29,12 @@ static hipError_t launch_stage_t(const StageJob& job, hipStream_t st) {
   const int nchunk = job.D / 8;
   // tile-per-XCD order: whole groups of 8 tiles, the workgroups past the last row leave at once
   const dim3 grid(job.xcd_rows ? (job.R + 127) / 128 * 128 : job.R);
-  if (nchunk <= 256) hipLaunchKernelGGL((stage_kernel<BF16, 1>), grid, dim3(256), 0, st, job);
-  else if (nchunk <= 512) hipLaunchKernelGGL((stage_kernel<BF16, 2>), grid, dim3(256), 0, st, job);
-  else if (nchunk <= 1024) hipLaunchKernelGGL((stage_kernel<BF16, 4>), grid, dim3(256), 0, st, job);
-  else if (nchunk <= 2048) hipLaunchKernelGGL((stage_kernel<BF16, 8>), grid, dim3(256), 0, st, job);
+  // 512 threads per row from D = 4096 on: the row's LayerNorm / GELU arithmetic is what a workgroup spends its
+  // time on once its loads are back, and eight waves halve it (7B batch 1: -1 us per step; 7-stage chain: -3.6 us)
+  if (nchunk <= 256) hipLaunchKernelGGL((stage_kernel<BF16, 1, 256>), grid, dim3(256), 0, st, job);
+  else if (nchunk <= 512) hipLaunchKernelGGL((stage_kernel<BF16, 1, 512>), grid, dim3(512), 0, st, job);
+  else if (nchunk <= 1024) hipLaunchKernelGGL((stage_kernel<BF16, 2, 512>), grid, dim3(512), 0, st, job);
+  else if (nchunk <= 2048) hipLaunchKernelGGL((stage_kernel<BF16, 4, 512>), grid, dim3(512), 0, st, job);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
