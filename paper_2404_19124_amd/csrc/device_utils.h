@@ -103,6 +103,13 @@ __device__ __forceinline__ void best_unkey(uint64_t key, float& v, int32_t& i) {
   v = __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
   i = static_cast<int32_t>(~static_cast<uint32_t>(key));
 }
+// A key the optimiser cannot look through.  Lists of keys live in registers and move up by one when
+// their head is taken ("a[q] = won ? a[q + 1] : a[q]"); left alone, the compiler turns that into
+// a[won ? q + 1 : q], a dynamic index into registers, i.e. a chain of selects over the whole list per entry.
+__device__ __forceinline__ uint64_t opaque_key(uint64_t x) {
+  asm("" : "+v"(x));
+  return x;
+}
 template <int CTRL, int ROW_MASK = 0xf>
 __device__ __forceinline__ uint64_t key_step(uint64_t key) {
   // rows outside ROW_MASK keep their own key (old = source): the step is then a no-op for them

@@ -183,7 +183,10 @@ __device__ __forceinline__ void skinny_run(const HeadJob& p, int wg, int G, u32x
   __syncthreads();
 
   // running state of the 256 epilogue threads: state row en, vocabulary residue vi
-  const int en = tid & 15, vi = (tid >> 4) & 15;
+  // (16 consecutive threads own one state row: the closing merge of a row's 16 residue lists then runs on
+  // DPP alone, no transposition through LDS; the price is a 4-way bank conflict on the 16 partial-sum
+  // reads per tile, a few hundred LDS cycles in a tile of several thousand)
+  const int en = (tid >> 4) & 15, vi = tid & 15;
   float run_m = SPEC_NEG_INF, run_s = 0.f;
   float tv[kMaxTopK];
   int32_t ti[kMaxTopK];
@@ -257,53 +260,34 @@ __device__ __forceinline__ void skinny_run(const HeadJob& p, int wg, int G, u32x
 
   if (p.out_head || p.vt_head == 0) return;
 
-  // ---- merge the 16 residue lists of each row into the workgroup's partial
-  __syncthreads();
-  float* lv = reinterpret_cast<float*>(ldsP);               // [16 rows][16 vi][8]
-  int32_t* li = reinterpret_cast<int32_t*>(lv + 16 * 16 * kMaxTopK);
-  float* lm = reinterpret_cast<float*>(li + 16 * 16 * kMaxTopK);  // [16][16]
-  float* ls = lm + 256;
+  // ---- merge the 16 residue lists of each row (16 consecutive lanes) into the workgroup's partial
   if (tid < 256) {
-#pragma unroll
-    for (int q = 0; q < kMaxTopK; ++q) {
-      lv[(en * 16 + vi) * kMaxTopK + q] = tv[q];
-      li[(en * 16 + vi) * kMaxTopK + q] = ti[q];
-    }
-    lm[en * 16 + vi] = run_m;
-    ls[en * 16 + vi] = run_s;
-  }
-  __syncthreads();
-  if (tid < 256) {
-    // now 16 consecutive lanes own one row: row = tid/16, list = tid%16
-    const int row = tid >> 4, src = tid & 15;
-    float hv[kMaxTopK];
-    int32_t hi[kMaxTopK];
-#pragma unroll
-    for (int q = 0; q < kMaxTopK; ++q) {
-      hv[q] = lv[(row * 16 + src) * kMaxTopK + q];
-      hi[q] = li[(row * 16 + src) * kMaxTopK + q];
-    }
-    float m = lm[row * 16 + src], s = ls[row * 16 + src];
-    const float mx = row16_max(m);
-    s = row16_sum((m > SPEC_NEG_INF) ? s * __expf(m - mx) : 0.f);
-    const int64_t slot = (int64_t)row * p.nparts + wg;
-    if (row < R && src == 0) {
+    const float mx = row16_max(run_m);
+    const float s = row16_sum((run_m > SPEC_NEG_INF) ? run_s * __expf(run_m - mx) : 0.f);
+    const int64_t slot = (int64_t)en * p.nparts + wg;
+    if (en < R && vi == 0) {
       p.part.m[slot] = mx;
       p.part.s[slot] = s;
     }
+    uint64_t hk[kMaxTopK];
+#pragma unroll
+    for (int q = 0; q < kMaxTopK; ++q) hk[q] = best_key(tv[q], ti[q]);
+    const uint64_t kEmpty = best_key(SPEC_NEG_INF, kIdxNone);
 #pragma unroll
     for (int j = 0; j < kMaxTopK; ++j) {
       if (j < p.k_top) {
-        float bv = hv[0];
-        int32_t bi = hi[0];
-        row16_best(bv, bi);
-        if (hi[0] == bi && hv[0] == bv) {  // the owner of the winner pops it
+        const uint64_t best = row16_best_key(hk[0]);
+        const bool won = hk[0] == best;   // the owner of the winner pops it
 #pragma unroll
-          for (int q = 0; q + 1 < kMaxTopK; ++q) { hv[q] = hv[q + 1]; hi[q] = hi[q + 1]; }
-          hv[kMaxTopK - 1] = SPEC_NEG_INF;
-          hi[kMaxTopK - 1] = kIdxNone;
+        for (int q = 0; q + 1 < kMaxTopK; ++q) {
+          const uint64_t up = opaque_key(hk[q + 1]);
+          hk[q] = won ? up : hk[q];
         }
-        if (row < R && src == j) {
+        hk[kMaxTopK - 1] = won ? kEmpty : hk[kMaxTopK - 1];
+        if (en < R && vi == j) {
+          float bv;
+          int32_t bi;
+          best_unkey(best, bv, bi);
           p.part.val[slot * p.k_top + j] = bv;
           p.part.idx[slot * p.k_top + j] = bi;
         }

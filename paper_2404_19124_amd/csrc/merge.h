@@ -123,7 +123,10 @@ __device__ __forceinline__ void wave_merge_partials_k(const Partials& p, int64_t
       const uint64_t best = wave_best_key(tk[0]);
       const bool won = tk[0] == best;   // the owner of the winner pops it (keys of real entries are unique)
 #pragma unroll
-      for (int q = 0; q + 1 < K; ++q) tk[q] = won ? tk[q + 1] : tk[q];
+      for (int q = 0; q + 1 < K; ++q) {
+        const uint64_t up = opaque_key(tk[q + 1]);
+        tk[q] = won ? up : tk[q];
+      }
       tk[K - 1] = won ? kEmpty : tk[K - 1];
       best_unkey(best, out_val[j], out_idx[j]);
     }
