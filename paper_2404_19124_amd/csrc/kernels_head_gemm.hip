@@ -829,56 +829,72 @@ __global__ __launch_bounds__(256, 1) void head_gemm32_kernel(GemmArgs p) {
   if (!any_head) return;
 
   // ---- merge the 8 lane lists of every row (2 K halves x 4 waves) into the workgroup's
-  // partial.  LDS aliases the slabs: the K loop ended on a barrier.
+  // partial.  LDS aliases the slabs: the K loop ended on a barrier.  The lists go to LDS as
+  // 64-bit keys, a row's 8 lists side by side (rows one key apart from a power of two: the
+  // writers of a wave hit distinct banks); then 8 adjacent lanes take one row, each its own
+  // list in registers, and softmax pieces and the k best are reduced over the 8 lanes on
+  // DPP - 32 rows per pass of the workgroup.  (One thread per row walking the 8 lists in
+  // LDS took 6-12k cycles at the end of a launch, 10 % of a single-tile launch.)
   constexpr int ROWS = 32 * MB;
-  float* sv = reinterpret_cast<float*>(smem);                  // [256][MB][KT]
-  int32_t* si = reinterpret_cast<int32_t*>(sv + 256 * MB * KT);
-  float* sm = reinterpret_cast<float*>(si + 256 * MB * KT);    // [256][MB]
-  float* ss = sm + 256 * MB;
+  constexpr int RS = 8 * KT + 1;
+  uint64_t* sk = reinterpret_cast<uint64_t*>(smem);            // [ROWS][RS]
+  float* sm = reinterpret_cast<float*>(sk + ROWS * RS);        // [ROWS][8]
+  float* ss = sm + ROWS * 8;
+  {
+    const int src = tid >> 5;   // this thread's place among the 8 that hold a row
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
+    for (int mb = 0; mb < MB; ++mb) {
+      const int rl = mb * 32 + c32;
 #pragma unroll
-    for (int q = 0; q < KT; ++q) {
-      sv[(tid * MB + mb) * KT + q] = lv[mb][q];
-      si[(tid * MB + mb) * KT + q] = li[mb][q];
+      for (int q = 0; q < KT; ++q) sk[rl * RS + src * KT + q] = best_key(lv[mb][q], li[mb][q]);
+      sm[rl * 8 + src] = run_m[mb];
+      ss[rl * 8 + src] = run_s[mb];
     }
-    sm[tid * MB + mb] = run_m[mb];
-    ss[tid * MB + mb] = run_s[mb];
   }
   __syncthreads();
-  for (int rl = tid; rl < ROWS; rl += 256) {
+  const uint64_t kEmpty = best_key(SPEC_NEG_INF, kIdxNone);
+#pragma unroll 1
+  for (int pass = 0; pass < MB; ++pass) {
+    const int rl = pass * 32 + (tid >> 3), s8 = tid & 7;
     const int r = mtile * ROWS + rl;
-    if (r >= p.R) continue;
-    const int mb = rl >> 5, c = rl & 31;
-    float mx = SPEC_NEG_INF;
-    for (int src = 0; src < 8; ++src) mx = fmaxf(mx, sm[(src * 32 + c) * MB + mb]);
-    float s = 0.f;
-    for (int src = 0; src < 8; ++src) {
-      const int th = src * 32 + c;
-      const float m = sm[th * MB + mb];
-      if (m > SPEC_NEG_INF) s += ss[th * MB + mb] * __expf(m - mx);
-    }
+    const bool live = r < p.R;
+    uint64_t hk[KT];
+#pragma unroll
+    for (int q = 0; q < KT; ++q) hk[q] = sk[rl * RS + s8 * KT + q];
+    const float m = sm[rl * 8 + s8], s = ss[rl * 8 + s8];
+    float mx = fmaxf(m, dpp_f<kDppXor1>(m));
+    mx = fmaxf(mx, dpp_f<kDppXor2>(mx));
+    mx = fmaxf(mx, dpp_f<kDppHalfMirror>(mx));
+    float sum = m > SPEC_NEG_INF ? s * __expf(m - mx) : 0.f;
+    sum += dpp_f<kDppXor1>(sum);
+    sum += dpp_f<kDppXor2>(sum);
+    sum += dpp_f<kDppHalfMirror>(sum);
     const int64_t slot = (int64_t)r * p.nparts + range;
-    p.part.m[slot] = mx;
-    p.part.s[slot] = s;
-    // 8-way merge of sorted lists: only the heads compete; 4-bit read positions packed in one word
-    uint32_t pos = 0;
-    for (int j = 0; j < p.k_top; ++j) {
-      float bv = SPEC_NEG_INF;
-      int32_t bi = kIdxNone;
-      int bsrc = 0;
-      for (int src = 0; src < 8; ++src) {
-        const int q = (int)((pos >> (4 * src)) & 15);
-        if (q < KT) {
-          const int th = src * 32 + c;
-          const float v = sv[(th * MB + mb) * KT + q];
-          const int32_t i = si[(th * MB + mb) * KT + q];
-          if (before(v, i, bv, bi)) { bv = v; bi = i; bsrc = src; }
+    if (live && s8 == 0) {
+      p.part.m[slot] = mx;
+      p.part.s[slot] = sum;
+    }
+#pragma unroll
+    for (int j = 0; j < KT; ++j) {
+      if (j < p.k_top) {
+        uint64_t best = key_step<kDppXor1>(hk[0]);
+        best = key_step<kDppXor2>(best);
+        best = key_step<kDppHalfMirror>(best);
+        const bool won = hk[0] == best;   // the owner of the winner pops it
+#pragma unroll
+        for (int q = 0; q + 1 < KT; ++q) {
+          const uint64_t up = opaque_key(hk[q + 1]);
+          hk[q] = won ? up : hk[q];
+        }
+        hk[KT - 1] = won ? kEmpty : hk[KT - 1];
+        if (live && s8 == j) {
+          float bv;
+          int32_t bi;
+          best_unkey(best, bv, bi);
+          p.part.val[slot * p.k_top + j] = bv;
+          p.part.idx[slot * p.k_top + j] = bi;
         }
       }
-      pos += 1u << (4 * bsrc);
-      p.part.val[slot * p.k_top + j] = bv;
-      p.part.idx[slot * p.k_top + j] = bi;
     }
   }
 }
