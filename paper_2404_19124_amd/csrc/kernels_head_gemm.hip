@@ -97,7 +97,8 @@ GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
   // 33..64 rows against a long weight matrix (at least one 256-row tile per two CUs): the
   // wide kernel re-reads the states a quarter as often per weight byte as the narrow one
   else if (R <= 64 && (int64_t)n_head + n_proj >= (int64_t)128 * (n_cu > 0 ? n_cu : 256)) {
-    pl.mi = 4; pl.ni = 4; pl.kcap = 8; pl.ts = 16;
+    pl.mi = 4; pl.ni = 4; pl.ts = 16;
+    pl.kcap = k_top <= 2 ? 2 : (k_top <= 4 ? 4 : (k_top <= 6 ? 6 : 8));
     fill_plan(pl, R, n_head, n_proj, n_cu);
     shrink_tile(pl, R, n_head, n_proj, n_cu);
     return pl;
@@ -111,10 +112,12 @@ GemmPlan plan_gemm(int R, int k_top, int n_head, int n_proj, int kt, int n_cu) {
     pl.kcap = 8;
   }
   else {
-    // wide kernel; the per-lane top-k lists are as short as k_top allows
+    // wide kernel; the per-lane top-k lists are as short as k_top allows (the epilogue of a tile is the
+    // insertion of every logit into them: its cost grows with their length, and a single-tile launch
+    // ends on it)
     pl.ni = 4;
     pl.ts = 16;
-    pl.kcap = k_top <= 2 ? 2 : (k_top <= 4 ? 4 : 8);
+    pl.kcap = k_top <= 4 ? (k_top < 2 ? 2 : k_top) : (k_top <= 6 ? 6 : 8);
     pl.mi = 6;
     fill_plan(pl, R, n_head, n_proj, n_cu);
     if (pl.kcap <= 4) {
@@ -992,28 +995,19 @@ hipError_t launch_head_gemm(const HeadJob& job, const GemmPlan& pl, hipStream_t 
   switch (key) {
     case 2 * 100 + 1 * 10 + 8: return launch_gemm_t<2, 1, 8>(a, st, ev_start, ev_stop, dry);
     case 4 * 100 + 1 * 10 + 8: return launch_gemm_t<4, 1, 8>(a, st, ev_start, ev_stop, dry);
+#define WIDE_CASE(MB_, KT_)                                                             \
+    case (2 * MB_) * 100 + 4 * 10 + KT_:                                                \
+      return vt ? launch_gemm32_t<MB_, 2, KT_, true>(a, st, ev_start, ev_stop, dry)      \
+                : launch_gemm32_t<MB_, 2, KT_, false>(a, st, ev_start, ev_stop, dry);
+    // 33..64 rows (always short tiles)
+    case 4 * 100 + 4 * 10 + 2: return launch_gemm32_t<2, 2, 2, true>(a, st, ev_start, ev_stop, dry);
+    case 4 * 100 + 4 * 10 + 4: return launch_gemm32_t<2, 2, 4, true>(a, st, ev_start, ev_stop, dry);
+    case 4 * 100 + 4 * 10 + 6: return launch_gemm32_t<2, 2, 6, true>(a, st, ev_start, ev_stop, dry);
     case 4 * 100 + 4 * 10 + 8: return launch_gemm32_t<2, 2, 8, true>(a, st, ev_start, ev_stop, dry);
-    case 6 * 100 + 4 * 10 + 2:
-      return vt ? launch_gemm32_t<3, 2, 2, true>(a, st, ev_start, ev_stop, dry)
-                : launch_gemm32_t<3, 2, 2, false>(a, st, ev_start, ev_stop, dry);
-    case 6 * 100 + 4 * 10 + 4:
-      return vt ? launch_gemm32_t<3, 2, 4, true>(a, st, ev_start, ev_stop, dry)
-                : launch_gemm32_t<3, 2, 4, false>(a, st, ev_start, ev_stop, dry);
-    case 6 * 100 + 4 * 10 + 8:
-      return vt ? launch_gemm32_t<3, 2, 8, true>(a, st, ev_start, ev_stop, dry)
-                : launch_gemm32_t<3, 2, 8, false>(a, st, ev_start, ev_stop, dry);
-    case 8 * 100 + 4 * 10 + 2:
-      return vt ? launch_gemm32_t<4, 2, 2, true>(a, st, ev_start, ev_stop, dry)
-                : launch_gemm32_t<4, 2, 2, false>(a, st, ev_start, ev_stop, dry);
-    case 8 * 100 + 4 * 10 + 4:
-      return vt ? launch_gemm32_t<4, 2, 4, true>(a, st, ev_start, ev_stop, dry)
-                : launch_gemm32_t<4, 2, 4, false>(a, st, ev_start, ev_stop, dry);
-    case 10 * 100 + 4 * 10 + 2:
-      return vt ? launch_gemm32_t<5, 2, 2, true>(a, st, ev_start, ev_stop, dry)
-                : launch_gemm32_t<5, 2, 2, false>(a, st, ev_start, ev_stop, dry);
-    case 10 * 100 + 4 * 10 + 4:
-      return vt ? launch_gemm32_t<5, 2, 4, true>(a, st, ev_start, ev_stop, dry)
-                : launch_gemm32_t<5, 2, 4, false>(a, st, ev_start, ev_stop, dry);
+    WIDE_CASE(3, 2) WIDE_CASE(3, 3) WIDE_CASE(3, 4) WIDE_CASE(3, 6) WIDE_CASE(3, 8)
+    WIDE_CASE(4, 2) WIDE_CASE(4, 3) WIDE_CASE(4, 4)
+    WIDE_CASE(5, 2) WIDE_CASE(5, 3) WIDE_CASE(5, 4)
+#undef WIDE_CASE
     default: return hipErrorInvalidValue;
   }
 }

@@ -86,12 +86,12 @@ PINNED = [
     ((1, 4096, 32000, 5, 4096), (0, 16, 16, 1, 256, 256, 1)),
     ((15, 4096, 32000, 2, 0), (0, 16, 16, 1, 256, 256, 1)),
     ((64, 4096, 0, 0, 4096), (1, 32, 64, 2, 64, 0, 4)),
-    ((64, 4096, 32000, 5, 4096), (1217, 64, 144, 1, 252, 223, 1)),
-    ((320, 4096, 32000, 3, 4096), (1408, 128, 256, 3, 85, 76, 1)),     # not launched like this: proj_apart
-    ((320, 4096, 32000, 3, 0), (1508, 160, 256, 2, 125, 125, 1)),      # the head alone: one tile per range
+    ((64, 4096, 32000, 5, 4096), (1213, 64, 144, 1, 252, 223, 1)),
+    ((320, 4096, 32000, 3, 4096), (1406, 128, 256, 3, 85, 76, 1)),     # not launched like this: proj_apart
+    ((320, 4096, 32000, 3, 0), (1506, 160, 256, 2, 125, 125, 1)),      # the head alone: one tile per range
     ((320, 4096, 0, 0, 4096), (1304, 96, 256, 4, 16, 0, 4)),           # the projection alone, four K parts
     ((960, 4096, 32000, 2, 0), (1504, 160, 256, 6, 42, 42, 1)),
-    ((384, 4096, 32000, 3, 0), (1308, 96, 256, 4, 64, 64, 1)),
+    ((384, 4096, 32000, 3, 0), (1306, 96, 256, 4, 64, 64, 1)),
     ((2304, 3072, 128256, 2, 0), (1504, 160, 256, 15, 17, 17, 1)),
 ]
 
