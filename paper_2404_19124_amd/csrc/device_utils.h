@@ -183,15 +183,21 @@ __device__ __forceinline__ float block_max(float x, float* scratch) {
 }
 template <int NT>
 __device__ __forceinline__ void block_best(float& v, int32_t& i, float* sv, int32_t* si) {
-  wave_best(v, i);
-  const int w = threadIdx.x >> 6, nw = NT / 64;
+  const uint64_t wk = wave_best_key(best_key(v, i));
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  constexpr int nw = NT / 64;
+  static_assert(nw <= 16, "the waves' results are combined by one row of 16 lanes");
   __syncthreads();
-  if ((threadIdx.x & 63) == 0) { sv[w] = v; si[w] = i; }
+  if (lane == 0) {
+    sv[w] = __uint_as_float(static_cast<uint32_t>(wk >> 32));
+    si[w] = static_cast<int32_t>(static_cast<uint32_t>(wk));
+  }
   __syncthreads();
-  v = sv[0];
-  i = si[0];
-  for (int j = 1; j < nw; ++j)
-    if (before(sv[j], si[j], v, i)) { v = sv[j]; i = si[j]; }
+  // the waves' keys, one per lane of a 16-lane row, reduced on DPP (every row computes the same)
+  const int l16 = lane & 15;
+  uint64_t key = 0;   // below every key
+  if (l16 < nw) key = (static_cast<uint64_t>(__float_as_uint(sv[l16])) << 32) | static_cast<uint32_t>(si[l16]);
+  best_unkey(row16_best_key(key), v, i);
 }
 
 }  // namespace specdraft

@@ -28,6 +28,8 @@ __global__ __launch_bounds__(NT) void argmax_rows_kernel(const void* logits, int
       return;
     }
   }
+  // (a thread meets its elements in increasing index order, so a strict "larger" keeps the first maximum;
+  // the (value, smaller index) order only matters between threads)
   float bv = SPEC_NEG_INF;
   int32_t bi = kIdxNone;
   if (BF16) {
@@ -52,20 +54,20 @@ __global__ __launch_bounds__(NT) void argmax_rows_kernel(const void* logits, int
             for (int q = 0; q < 4; ++q) {
               const float lo = bf16_bits_to_f32(raw[u][q] & 0xffffu), hi = bf16_bits_to_f32(raw[u][q] >> 16);
               const int i0 = c * 8 + 2 * q;
-              if (before(lo, i0, bv, bi)) { bv = lo; bi = i0; }
-              if (before(hi, i0 + 1, bv, bi)) { bv = hi; bi = i0 + 1; }
+              if (lo > bv) { bv = lo; bi = i0; }
+              if (hi > bv) { bv = hi; bi = i0 + 1; }
             }
           }
         }
       }
       for (int i = (V / 8) * 8 + tid; i < V; i += NT) {
         const float v = bf16_bits_to_f32(x[i]);
-        if (before(v, i, bv, bi)) { bv = v; bi = i; }
+        if (v > bv) { bv = v; bi = i; }
       }
     } else {
       for (int i = tid; i < V; i += NT) {
         const float v = bf16_bits_to_f32(x[i]);
-        if (before(v, i, bv, bi)) { bv = v; bi = i; }
+        if (v > bv) { bv = v; bi = i; }
       }
     }
   } else {
@@ -84,18 +86,18 @@ __global__ __launch_bounds__(NT) void argmax_rows_kernel(const void* logits, int
           if (c < nvec) {
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-              if (before(r[u][q], c * 4 + q, bv, bi)) { bv = r[u][q]; bi = c * 4 + q; }
+              if (r[u][q] > bv) { bv = r[u][q]; bi = c * 4 + q; }
           }
         }
       }
       for (int i = (V / 4) * 4 + tid; i < V; i += NT) {
         const float v = x[i];
-        if (before(v, i, bv, bi)) { bv = v; bi = i; }
+        if (v > bv) { bv = v; bi = i; }
       }
     } else {
       for (int i = tid; i < V; i += NT) {
         const float v = x[i];
-        if (before(v, i, bv, bi)) { bv = v; bi = i; }
+        if (v > bv) { bv = v; bi = i; }
       }
     }
   }
