@@ -65,6 +65,10 @@ SMALL_BF16 = [
     ("bf16_chain_n7", 128, 128, 500, 7, (1,) * 7, 1, 2),    # k = 1 chain, 7 heads
     ("bf16_b1_n5", 128, 128, 500, 5, (2, 2, 1, 2, 1), 5, 1),
     ("bf16_b40_long_vocab", 64, 64, 33000, 2, (2, 2), 4, 40),  # 40, 80 rows: wide kernel with 64-row blocks
+    # the same 64-row instance with per-lane lists of 4, 6 and 8 entries (top-k 4, 6, 8), 64 and 33 rows
+    ("bf16_b40_long_vocab_k4", 64, 64, 33000, 2, (4, 1), 4, 40),
+    ("bf16_b64_long_vocab_k6", 64, 64, 33000, 2, (6, 1), 6, 64),
+    ("bf16_b33_long_vocab_k8", 64, 64, 33000, 2, (8, 1), 8, 33),
     # 160-row state blocks of the wide kernel (chosen when 96-row blocks would need two tiles per range):
     # 5 K slabs = one steady group + tail, ragged vocabulary and rows; per-lane lists of 2 and of 4
     ("bf16_b31_tall_k2", 128, 320, 16500, 3, (5, 3, 2), 6, 31),   # 31, 155, 465
