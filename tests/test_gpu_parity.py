@@ -69,6 +69,8 @@ SMALL_BF16 = [
     ("bf16_b40_long_vocab_k4", 64, 64, 33000, 2, (4, 1), 4, 40),
     ("bf16_b64_long_vocab_k6", 64, 64, 33000, 2, (6, 1), 6, 64),
     ("bf16_b33_long_vocab_k8", 64, 64, 33000, 2, (8, 1), 8, 33),
+    # more than 64 rows with top-k 6 and 3: 96-row blocks with per-lane lists of 6 and of 3 entries
+    ("bf16_b70_k6", 64, 128, 2049, 2, (6, 3), 8, 70),
     # 160-row state blocks of the wide kernel (chosen when 96-row blocks would need two tiles per range):
     # 5 K slabs = one steady group + tail, ragged vocabulary and rows; per-lane lists of 2 and of 4
     ("bf16_b31_tall_k2", 128, 320, 16500, 3, (5, 3, 2), 6, 31),   # 31, 155, 465
